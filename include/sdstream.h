@@ -1,0 +1,154 @@
+/*
+ * sdstream - the Stream Batch denoising step of StreamDiffusion (arXiv 2312.12491) for AMD MI355X (gfx950).
+ *
+ * One handle owns one static-shape denoising engine: the weights of a latent-diffusion U-Net, the rolling
+ * latent queue of Sec. 3.1, the per-slot reference latents needed by residual classifier-free guidance
+ * (Sec. 3.3), the pre-computed caches of the appendix "Pre-computation" (per-step noise, sqrt(alpha)/sqrt(beta),
+ * time-embedding biases, cross-attention K/V of the prompt) and the reference image of the stochastic
+ * similarity filter (Sec. 3.4).  Shapes are fixed at creation, as the paper fixes them per engine (appendix,
+ * "Model Acceleration"): a new shape needs a new handle.
+ *
+ * Conventions
+ *   - Every function returns SDSTREAM_OK (0) or a negative SDSTREAM_E_* code; nothing throws or aborts.  After a
+ *     failure sdstream_last_error() gives a message and the handle's queue state is unchanged.
+ *   - "host" / "device" on a pointer says where the memory lives.  The library never keeps, frees or writes a
+ *     caller's input pointer after the call returns (device inputs must stay valid until the stream has run).
+ *   - Tensors at the boundary are float32, latents NCHW [.,C,H,W], contexts row-major [L,D].
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls enqueue work and return
+ *     without synchronising unless stated otherwise.
+ *   - A handle may be used by one thread at a time.
+ */
+#ifndef SDSTREAM_H
+#define SDSTREAM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SDSTREAM_OK 0
+#define SDSTREAM_E_INVALID_ARG (-1)
+#define SDSTREAM_E_NOT_READY (-2)
+#define SDSTREAM_E_SHAPE (-3)
+#define SDSTREAM_E_NOMEM (-4)
+#define SDSTREAM_E_HIP (-5)
+
+#define SDSTREAM_MAX_LEVELS 8
+
+/* cfg_mode: which noise the scheduler update sees */
+#define SDSTREAM_CFG_NONE 0    /* eps_c                                                        */
+#define SDSTREAM_CFG_FULL 1    /* Eq. 2, 2n U-Net rows per frame                               */
+#define SDSTREAM_CFG_SELF 2    /* Eq. 5-6 with the input latent as reference, n rows           */
+#define SDSTREAM_CFG_ONETIME 3 /* Eq. 5-7, reference from one negative-prompt row, n+1 rows    */
+
+typedef struct sdstream sdstream_t;
+
+typedef struct {
+  int32_t in_channels;                          /* latent channels (4)                                         */
+  int32_t n_levels;                             /* resolution levels of the U-Net                              */
+  int32_t block_channels[SDSTREAM_MAX_LEVELS];  /* width per level, e.g. 320,640,1280,1280                     */
+  int32_t layers_per_block;                     /* ResBlocks per level on the way down (one more on the way up)*/
+  uint32_t attn_level_mask;                     /* bit l: a transformer follows every ResBlock of level l      */
+  int32_t num_heads;                            /* exactly one of num_heads / head_dim is > 0                  */
+  int32_t head_dim;
+  int32_t mid_attention;                        /* transformer between the two middle ResBlocks                */
+  int32_t context_len, context_dim;             /* prompt embedding [L,D]                                      */
+  int32_t norm_groups;                          /* GroupNorm groups                                            */
+  int32_t latent_h, latent_w;
+  int32_t dtype;                                /* 0: float32 storage and arithmetic; 1: bf16 storage, MFMA    */
+  int32_t n_denoise;                            /* n = Stream Batch size = denoising steps                     */
+  int32_t n_streams;                            /* S independent streams sharing weights, noise and prompt     */
+  int32_t cfg_mode;                             /* SDSTREAM_CFG_*                                              */
+  int32_t scheduler;                            /* 0: LCM re-noising with the cached noise; 1: DDIM (eta = 0)  */
+} sdstream_config;
+
+/* Creates an engine on the current HIP device and allocates all device state.  No weights yet. */
+int sdstream_create(const sdstream_config* cfg, sdstream_t** out);
+void sdstream_destroy(sdstream_t* h);
+const char* sdstream_last_error(const sdstream_t* h); /* h may be NULL: message of the last failed create */
+
+/* Weight manifest: the order, names, shapes (conv OIHW, linear [out,in]) and kinds
+ * (0 weight, 1 bias, 2 norm scale, 3 norm shift) of the tensors in the blob load_weights expects. */
+int64_t sdstream_param_count(const sdstream_t* h);
+int32_t sdstream_manifest_size(const sdstream_t* h);
+int sdstream_manifest_entry(const sdstream_t* h, int32_t index, char* name, size_t name_cap, int32_t shape[4],
+                            int32_t* ndim, int32_t* kind);
+
+/* host_blob: host, float32, all tensors of the manifest back to back; `bytes` must equal 4 * param_count.
+ * The library copies, converts (bf16 round-to-nearest-even when dtype = 1) and repacks; synchronous. */
+int sdstream_load_weights(sdstream_t* h, const void* host_blob, size_t bytes);
+
+/* alphas_cumprod: host, [1000] (alpha of Eq. 1 per timestep); NULL restores the built-in scaled-linear table.
+ * Resets the queue. */
+int sdstream_set_schedule(sdstream_t* h, const float* alphas_cumprod);
+
+/* The pre-sampled noise of the appendix: host, [n][S][C][H][W], fixed for the session.  Resets the queue. */
+int sdstream_set_noise(sdstream_t* h, const float* host_noise);
+
+/* One pass of Sec. 3.1: takes one clean latent per stream, advances every queued latent one denoising step
+ * (noise-in Eq. 1, batched U-Net, guidance Eq. 2 / Eq. 5-7, update Eq. 4, re-noise, queue shift) and writes the
+ * latent that has finished its n-th step.
+ *   x0_in        device [S,C,H,W]
+ *   context      device [L,D] prompt embedding; neg_context likewise, required for CFG_FULL and CFG_ONETIME
+ *   context_epoch the cross-attention K/V cache is rebuilt only when this value differs from the last call's
+ *   timesteps    host [n], strictly decreasing, each in [0,999]; a change recomputes the caches, resets the queue
+ *   gamma, delta guidance scale and residual-noise scale of Eq. 6 (ignored for CFG_NONE)
+ *   out_latent   device [S,C,H,W]: x0-prediction of the frame given n-1 calls earlier
+ *   out_valid    host, may be NULL: 0 during the first n-1 calls after a reset, else 1 */
+int sdstream_step(sdstream_t* h, const float* x0_in, const float* context, const float* neg_context,
+                  uint64_t context_epoch, const int32_t* timesteps, float gamma, float delta, float* out_latent,
+                  int32_t* out_valid, void* hip_stream);
+
+/* The U-Net alone (the eps_theta of Sec. 3.1), for checking it apart from the queue:
+ *   x device [N,C,H,W], t host [N] in [0,999], ctx device [L,D], eps_out device [N,C,H,W];
+ *   1 <= N <= sdstream_max_batch(h).  Does not touch the queue. */
+int sdstream_unet_forward(sdstream_t* h, const float* x, const int32_t* t, const float* ctx, int32_t n,
+                          float* eps_out, void* hip_stream);
+int32_t sdstream_max_batch(const sdstream_t* h);
+
+/* Stochastic similarity filter (Eq. 8-9) on one raw frame: device, uint8 [h*w*3].  Computes the cosine
+ * similarity with the stored reference frame from exact integer sums, the skip probability for threshold eta
+ * and the decision u_k < P with u_k the counter-based uniform of (seed, frame_index) (see sdstream_ssf_decide).
+ * A frame that is not skipped becomes the reference.  The first frame after create/reset is never skipped.
+ * Synchronises the stream (it returns a decision).  skip: host; prob: host, may be NULL. */
+int sdstream_ssf(sdstream_t* h, const uint8_t* frame, int32_t height, int32_t width, double eta, uint64_t seed,
+                 uint64_t frame_index, int32_t* skip, double* prob, void* hip_stream);
+
+/* The host half of the filter, usable without a GPU: given dot = I_t.I_ref, n_t = |I_t|^2, n_ref = |I_ref|^2,
+ * returns 1 to skip, 0 to process.  S_C = min(1, dot / sqrt(n_t * n_ref)) in double; P = max(0,(S_C-eta)/(1-eta)),
+ * P = 0 when eta >= 1 or a norm is zero; u = (mix(seed + (frame_index+1)*0x9E3779B97F4A7C15) >> 11) * 2^-53 with
+ * mix the SplitMix64 output function; skip iff u < P. */
+int sdstream_ssf_decide(uint64_t dot, uint64_t n_t, uint64_t n_ref, double eta, uint64_t seed, uint64_t frame_index,
+                        double* prob);
+
+/* Clears the queue, the reference latents, the filter's reference frame and the warm-up counter. */
+int sdstream_reset(sdstream_t* h);
+
+/* Multiply-add work of one U-Net row as 2*M*N*K summed over every convolution, linear layer and attention
+ * product that runs per step (cached K/V projections and the time-embedding path excluded). */
+double sdstream_flops_per_row(const sdstream_t* h);
+
+/* Per-kernel-class timing.  While enabled, sdstream_step / sdstream_unet_forward launch kernel by kernel with
+ * HIP events around each launch on the caller's stream (no graph replay) and accumulate per class.
+ * sdstream_profile_read synchronises and copies up to `cap` classes: name (<= 31 chars), launches, total
+ * milliseconds, algorithmic flops and algorithmic bytes; returns the number of classes. */
+typedef struct {
+  char name[32];
+  int64_t launches;
+  double ms;
+  double flops;
+  double bytes;
+} sdstream_profile_entry;
+int sdstream_profile_enable(sdstream_t* h, int32_t on);
+int sdstream_profile_reset(sdstream_t* h);
+int32_t sdstream_profile_read(sdstream_t* h, sdstream_profile_entry* out, int32_t cap);
+
+/* 0: launch kernels one by one; 1 (default): replay the step as a HIP graph captured on first use. */
+int sdstream_use_graph(sdstream_t* h, int32_t on);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SDSTREAM_H */

@@ -1,0 +1,128 @@
+// Shared declarations of the sdstream HIP library: storage types, kernel parameter blocks, launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef __bf16 bf16_t;
+
+template <typename T> __device__ __forceinline__ float to_f32(T v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }
+
+enum { EPI_NONE = 0, EPI_GEGLU = 1, EPI_SILU = 2 };
+
+// C[M,N] = gather(A)[M,K] * W[N,K]^T (+ bias, + per-sample bias, activation, + residual).
+// A is the implicit im2col matrix of one or two NHWC activations (channel concat): row m = (sample, oy, ox),
+// column k = tap * (C1+C2) + c with tap = ky*ksize + kx; source pixel (oy*stride + ky - pad, ox*stride + kx - pad)
+// in the (optionally nearest-2x upsampled) input, zero outside.  Linear layers are ksize = 1 over "pixels" = tokens.
+struct IgemmParams {
+  const void* src1;
+  const void* src2;
+  int C1, C2;
+  int Hin, Win;      // stored size of the sources
+  int Hout, Wout;
+  int ksize, stride, upsample;
+  int M, N, K;
+  const void* W;         // layout depends on the kernel (generic: [N][K]; MFMA: fragment-packed)
+  const float* bias;     // [N] or null
+  const float* rowbias;  // [samples][rowbias_ld] or null (time-embedding bias of a ResBlock)
+  int rowbias_ld;
+  const void* residual;  // [M][Nout] or null
+  void* out;             // [M][Nout], Nout = N (N/2 for GEGLU)
+  int epilogue;
+  int splitk;            // MFMA kernel only: number of K splits (fp32 atomics into `workspace`)
+  float* workspace;
+};
+
+struct GroupNormParams {
+  const void* src1;
+  const void* src2;
+  int C1, C2, HW, groups, samples;
+  float eps;
+  int silu;
+  const float* gamma;
+  const float* beta;
+  float* stats;  // [samples*groups][2] scratch: mean, rstd
+  void* out;     // [samples][HW][C1+C2]
+};
+
+struct LayerNormParams {
+  const void* src;
+  int rows, C;
+  float eps;
+  const float* gamma;
+  const float* beta;
+  void* out;
+};
+
+// softmax(q k^T / sqrt(d)) v per (sample, head).  q/k/v/out are row-major with their own leading dimensions
+// so fused QKV buffers can be addressed in place; head h uses columns [h*d, (h+1)*d).
+struct AttnParams {
+  const void* q;
+  const void* k;
+  const void* v;
+  void* out;
+  int ldq, ldk, ldv, ldo;
+  int Sq, Skv, heads, d, samples;
+  long long kv_sample_stride;   // elements between samples in k/v (0 with kv_select: cached prompt K/V)
+  const int* kv_select;         // per sample: which cached context (0 positive, 1 negative) or null
+  long long kv_select_stride;   // elements between cached contexts
+  float scale;
+};
+
+template <typename T> void launch_igemm_generic(const IgemmParams& p, hipStream_t s);
+void launch_igemm_mfma(const IgemmParams& p, hipStream_t s);
+bool igemm_mfma_supported(const IgemmParams& p);
+bool igemm_mfma_available();
+template <typename T> void launch_group_norm(const GroupNormParams& p, hipStream_t s);
+template <typename T> void launch_layer_norm(const LayerNormParams& p, hipStream_t s);
+template <typename T> void launch_attention_generic(const AttnParams& p, hipStream_t s);
+void launch_attention_mfma(const AttnParams& p, hipStream_t s);
+bool attention_mfma_supported(const AttnParams& p);
+
+// conv_in: fp32 NCHW [N,Cin,H,W] -> T NHWC [N,HW,C0]; w fp32 OIHW, 3x3 pad 1.
+template <typename T>
+void launch_conv_in(const float* x, const float* w, const float* b, void* out, int N, int Cin, int H, int W, int C0,
+                    hipStream_t s);
+// conv_out: T NHWC [N,HW,C0] -> fp32 NCHW [N,Cout,H,W]; w T [Cout][9][C0] (tap-major), 3x3 pad 1.
+template <typename T>
+void launch_conv_out(const void* x, const void* w, const float* b, float* out, int N, int Cout, int H, int W, int C0,
+                     hipStream_t s);
+
+// e[row] = [cos(t f_j) ; sin(t f_j)], f_j = exp(-ln(1e4) j/half), evaluated in double.
+void launch_time_embedding(const int* t, float* out, int rows, int C0, hipStream_t s);
+
+struct StreamParams {
+  int S, n, E;           // streams, denoising steps, elements per latent
+  int mode, scheduler;
+  float gamma, delta;
+  const float* a;        // [n] sqrt(alpha), device
+  const float* b;        // [n] sqrt(beta), device
+  const float* noise;    // [n][S][E]
+  const float* x0_in;    // [S][E]
+  float* xcur;           // [rows][E] U-Net input batch of this call
+  float* xnext;          // the next call's batch (rows i+1 written by the tail)
+  float* rcur;           // [S*n][E] reference latents, same row order
+  float* rnext;
+  const float* eps;      // [rows][E] U-Net output
+  float* out;            // [S][E]
+};
+void launch_stream_head(const StreamParams& p, hipStream_t s);
+void launch_stream_tail(const StreamParams& p, hipStream_t s);
+
+// SSF: dot(frame, ref) and |frame|^2 as exact 64-bit integers into sums[0..1]; copies frame to spare.
+void launch_ssf_reduce(const uint8_t* frame, const uint8_t* ref, uint8_t* spare, long long n, unsigned long long* sums,
+                       hipStream_t s);
+
+// Weight repacking from the canonical fp32 layouts.  All run on device from a staging copy.
+//  conv OIHW [O][I][kh][kw] -> T [O][kh*kw][I] (tap-major K), optionally GEGLU row interleave
+template <typename T>
+void launch_repack_rowmajor(const float* src, void* dst, int O, int I, int taps, int geglu_block, hipStream_t s);
+void launch_repack_mfma(const float* src, void* dst, int O, int I, int taps, int geglu_block, hipStream_t s);
+void launch_permute_bias(const float* src, float* dst, int O, int geglu_block, hipStream_t s);
+template <typename T> void launch_convert(const float* src, void* dst, long long n, hipStream_t s);
+void launch_fill_u32(void* dst, unsigned v, long long n_words, hipStream_t s);
+void launch_copy_rows_f32(const float* src, float* dst, long long n, hipStream_t s);

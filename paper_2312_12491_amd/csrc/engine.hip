@@ -1,0 +1,1252 @@
+// Host side of libsdstream: configuration, weight manifest and repacking, the static U-Net plan,
+// the Stream Batch state machine and the C ABI declared in include/sdstream.h.
+#include "common.h"
+#include "sdstream.h"
+
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <map>
+#include <string>
+#include <vector>
+
+namespace {
+
+thread_local std::string g_create_error;
+
+// ------------------------------------------------------------------------------------------------
+// plan-time interval allocator (first fit, coalescing).  Offsets are in bytes for ONE sample; the
+// arena holds max_batch times that, sample-major per buffer, so a smaller batch uses a prefix.
+// ------------------------------------------------------------------------------------------------
+struct Interval {
+  size_t off, size;
+  bool free;
+};
+struct PlanAllocator {
+  std::vector<Interval> iv;
+  size_t peak = 0;
+  size_t alloc(size_t bytes) {
+    bytes = (bytes + 255) & ~(size_t)255;
+    for (size_t i = 0; i < iv.size(); ++i) {
+      if (iv[i].free && iv[i].size >= bytes) {
+        if (iv[i].size > bytes) {
+          Interval rest{iv[i].off + bytes, iv[i].size - bytes, true};
+          iv[i].size = bytes;
+          iv.insert(iv.begin() + i + 1, rest);
+        }
+        iv[i].free = false;
+        return iv[i].off;
+      }
+    }
+    // grow: extend a trailing free interval or append
+    if (!iv.empty() && iv.back().free) {
+      iv.back().size = bytes;
+      iv.back().free = false;
+      peak = iv.back().off + bytes;
+      return iv.back().off;
+    }
+    Interval n{peak, bytes, false};
+    iv.push_back(n);
+    peak += bytes;
+    return n.off;
+  }
+  void release(size_t off) {
+    for (size_t i = 0; i < iv.size(); ++i) {
+      if (iv[i].off == off && !iv[i].free) {
+        iv[i].free = true;
+        if (i + 1 < iv.size() && iv[i + 1].free) {
+          iv[i].size += iv[i + 1].size;
+          iv.erase(iv.begin() + i + 1);
+        }
+        if (i > 0 && iv[i - 1].free) {
+          iv[i - 1].size += iv[i].size;
+          iv.erase(iv.begin() + i);
+        }
+        return;
+      }
+    }
+  }
+};
+
+enum OpKind { OP_IGEMM, OP_GN, OP_LN, OP_ATTN, OP_CONV_IN, OP_CONV_OUT };
+enum ProfClass {
+  PC_IGEMM_MFMA, PC_IGEMM_VALU, PC_ATTN_MFMA, PC_ATTN_VALU, PC_GROUP_NORM, PC_LAYER_NORM, PC_CONV_IN, PC_CONV_OUT,
+  PC_STREAM_HEAD, PC_STREAM_TAIL, PC_COUNT
+};
+const char* kProfNames[PC_COUNT] = {"igemm_mfma", "igemm_valu", "attn_mfma", "attn_valu", "group_norm",
+                                    "layer_norm", "conv_in", "conv_out", "stream_head", "stream_tail"};
+
+struct Op {
+  OpKind kind;
+  int cls;
+  bool mfma;
+  IgemmParams g;
+  GroupNormParams gn;
+  LayerNormParams ln;
+  AttnParams at;
+  int rows_per_sample;   // output pixels / tokens per sample
+  double flops_per_row;  // algorithmic multiply-add work per sample
+  double bytes_per_row;  // algorithmic bytes per sample (activations in + out)
+  double bytes_fixed;    // weights
+  // conv_in / conv_out
+  const float* cw_f32;
+  const void* cw;
+  const float* cb;
+  const void* cin;
+  void* cout_;
+};
+
+enum LoadAction { LA_F32, LA_ROWMAJOR, LA_MFMA, LA_BIAS_PERM };
+struct Entry {
+  std::string name;
+  int shape[4];
+  int ndim;
+  int kind;  // 0 weight 1 bias 2 gamma 3 beta
+  size_t count;
+  int action;
+  size_t dst_off;  // bytes into the weight arena
+  int O, I, taps, geglu;
+};
+
+struct LinW {
+  size_t w = 0, b = 0;  // byte offsets into the weight arena (b: fp32)
+  int N = 0, K = 0;
+  bool mfma = false;
+  bool has_bias = false;
+};
+
+struct KVSite {
+  LinW w;        // fused [2C][D]
+  size_t cache;  // byte offset in the persistent arena: [2][L][2C] T
+  int C;
+};
+
+}  // namespace
+
+struct sdstream {
+  sdstream_config cfg;
+  std::string err;
+  int elt = 4;  // bytes per activation element
+  int max_batch = 0;
+  int E = 0;  // elements per latent
+  bool use_mfma = false;
+
+  std::vector<Entry> manifest;
+  int64_t n_params = 0;
+  size_t weight_bytes = 0;
+  char* weights = nullptr;
+  bool weights_loaded = false;
+
+  // activations
+  PlanAllocator act;
+  char* act_base = nullptr;
+  size_t act_bytes = 0;
+  // persistent buffers (temb biases, kv caches, state), plain bump allocation in bytes
+  size_t persist_bytes = 0;
+  char* persist = nullptr;
+
+  std::vector<Op> ops;       // the U-Net
+  std::vector<Op> temb_ops;  // time-embedding path (float32)
+  std::vector<KVSite> kv_sites;
+  size_t off_emb = 0, off_h1 = 0, off_h2 = 0, off_tdev = 0, off_ctxT = 0;
+  size_t off_sel_zero = 0, off_sel_step = 0;
+  size_t off_x[2] = {0, 0}, off_r[2] = {0, 0}, off_eps = 0, off_noise = 0, off_ab = 0;
+  size_t off_unet_x = 0;  // fp32 input batch for unet_forward
+  double flops_per_row = 0;
+
+  // state
+  std::vector<int> temb_cached;  // timesteps the temb buffers hold
+  std::vector<int> timesteps;    // of the stream
+  bool have_noise = false;
+  bool kv_valid = false;
+  bool kv_for_step = false;
+  uint64_t kv_epoch = 0;
+  int cur = 0;
+  long long calls = 0;
+  double alphas[1000];
+
+  // ssf
+  uint8_t* ssf_buf[2] = {nullptr, nullptr};
+  unsigned long long* ssf_sums = nullptr;  // device [4]
+  unsigned long long* ssf_host = nullptr;  // pinned [4]
+  long long ssf_n = 0;
+  int ssf_ref = -1;
+  uint64_t ssf_ref_norm = 0;
+
+  // graph
+  bool graph_enabled = true;
+  hipStream_t cap_stream = nullptr;
+  std::map<int, hipGraphExec_t> graphs;
+
+  // profiling
+  bool profiling = false;
+  struct ProfRec { int cls; hipEvent_t a, b; double flops, bytes; };
+  std::vector<ProfRec> prof_pending;
+  sdstream_profile_entry prof[PC_COUNT];
+};
+
+namespace {
+
+int fail(sdstream* h, int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (h) h->err = buf; else g_create_error = buf;
+  return code;
+}
+
+#define HIP_TRY(h, expr)                                                                       \
+  do {                                                                                         \
+    hipError_t e_ = (expr);                                                                    \
+    if (e_ != hipSuccess) return fail(h, SDSTREAM_E_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+// ------------------------------------------------------------------------------------------------
+// builder: walks the U-Net once, registering weights (manifest + device layout) and emitting ops
+// ------------------------------------------------------------------------------------------------
+struct Builder {
+  sdstream& e;
+  bool dry;  // first pass: sizes only (pointers are offsets from null)
+  size_t wbytes = 0, pbytes = 0;
+  int temb_dim;
+
+  explicit Builder(sdstream& eng, bool dry_) : e(eng), dry(dry_) { temb_dim = 4 * eng.cfg.block_channels[0]; }
+
+  // ---- weights
+  size_t walloc(size_t bytes) {
+    size_t off = wbytes;
+    wbytes += (bytes + 255) & ~(size_t)255;
+    return off;
+  }
+  size_t palloc(size_t bytes) {
+    size_t off = pbytes;
+    pbytes += (bytes + 255) & ~(size_t)255;
+    return off;
+  }
+  void add_entry(const std::string& name, std::initializer_list<int> shape, int kind, int action, size_t dst_off, int O,
+                 int I, int taps, int geglu) {
+    Entry en;
+    en.name = name;
+    en.ndim = (int)shape.size();
+    en.count = 1;
+    int i = 0;
+    for (int s : shape) { en.shape[i++] = s; en.count *= (size_t)s; }
+    for (; i < 4; ++i) en.shape[i] = 1;
+    en.kind = kind;
+    en.action = action;
+    en.dst_off = dst_off;
+    en.O = O; en.I = I; en.taps = taps; en.geglu = geglu;
+    if (dry) e.manifest.push_back(en);
+  }
+  float* fvec(const std::string& name, int n, int kind) {
+    size_t off = walloc((size_t)n * 4);
+    add_entry(name, {n}, kind, LA_F32, off, n, 1, 1, 0);
+    return (float*)(e.weights + off);
+  }
+  bool mfma_ok(int C1, int C2, int N, bool geglu) const {
+    if (!e.use_mfma || !igemm_mfma_available()) return false;
+    if (C1 % 32 || C2 % 32) return false;
+    if (N % 16) return false;
+    if (geglu && N % 32) return false;
+    return true;
+  }
+  // a conv / linear weight in the activation dtype; `ksz` 1 or 3; canonical shape OIHW or [O,I]
+  LinW matw(const std::string& name, int O, int I, int ksz, bool conv_shape, bool bias, bool geglu, int C1, int C2) {
+    LinW w;
+    int taps = ksz * ksz;
+    w.N = O;
+    w.K = I * taps;
+    w.mfma = mfma_ok(C1, C2, O, geglu);
+    w.w = walloc((size_t)O * w.K * e.elt);
+    int blk = geglu ? (w.mfma ? 16 : 1) : 0;
+    if (conv_shape)
+      add_entry(name + ".w", {O, I, ksz, ksz}, 0, w.mfma ? LA_MFMA : LA_ROWMAJOR, w.w, O, I, taps, blk);
+    else
+      add_entry(name + ".w", {O, I}, 0, w.mfma ? LA_MFMA : LA_ROWMAJOR, w.w, O, I, taps, blk);
+    if (bias) {
+      w.b = walloc((size_t)O * 4);
+      w.has_bias = true;
+      add_entry(name + ".b", {O}, 1, geglu ? LA_BIAS_PERM : LA_F32, w.b, O, 1, 1, blk);
+    }
+    return w;
+  }
+  // several [C,I] matrices stacked along the output dimension (fused q/k/v), no bias
+  LinW fused(const std::vector<std::string>& names, int C, int I) {
+    LinW w;
+    int n = (int)names.size();
+    w.N = n * C;
+    w.K = I;
+    w.mfma = mfma_ok(I, 0, C, false);
+    w.w = walloc((size_t)w.N * I * e.elt);
+    for (int j = 0; j < n; ++j)
+      add_entry(names[j] + ".w", {C, I}, 0, w.mfma ? LA_MFMA : LA_ROWMAJOR, w.w + (size_t)j * C * I * e.elt, C, I, 1, 0);
+    return w;
+  }
+  // fp32 [O][I] matrix + bias for the time-embedding path
+  LinW f32w(const std::string& name, int O, int I) {
+    LinW w;
+    w.N = O; w.K = I; w.mfma = false; w.has_bias = true;
+    w.w = walloc((size_t)O * I * 4);
+    add_entry(name + ".w", {O, I}, 0, LA_F32, w.w, O, I, 1, 0);
+    w.b = walloc((size_t)O * 4);
+    add_entry(name + ".b", {O}, 1, LA_F32, w.b, O, 1, 1, 0);
+    return w;
+  }
+
+  // ---- activations
+  void* aalloc(size_t elems_per_sample) {
+    size_t off = e.act.alloc(elems_per_sample * e.elt);
+    return e.act_base + off * (size_t)e.max_batch;
+  }
+  void afree(void* p) { e.act.release((size_t)((char*)p - e.act_base) / (size_t)e.max_batch); }
+
+  // ---- ops
+  void* conv(const void* s1, int C1, const void* s2, int C2, int Hin, int Win, int Hout, int Wout, int ks, int stride,
+             int ups, const LinW& w, const float* rowbias, int rowbias_ld, const void* residual, int epi) {
+    Op op{};
+    op.kind = OP_IGEMM;
+    op.mfma = w.mfma;
+    op.cls = w.mfma ? PC_IGEMM_MFMA : PC_IGEMM_VALU;
+    IgemmParams& g = op.g;
+    g.src1 = s1; g.src2 = s2; g.C1 = C1; g.C2 = C2;
+    g.Hin = Hin; g.Win = Win; g.Hout = Hout; g.Wout = Wout;
+    g.ksize = ks; g.stride = stride; g.upsample = ups;
+    g.N = w.N; g.K = ks * ks * (C1 + C2);
+    g.W = e.weights + w.w;
+    g.bias = w.has_bias ? (const float*)(e.weights + w.b) : nullptr;
+    g.rowbias = rowbias; g.rowbias_ld = rowbias_ld;
+    g.residual = residual;
+    g.epilogue = epi;
+    g.splitk = 1;
+    int Nout = epi == EPI_GEGLU ? w.N / 2 : w.N;
+    g.out = aalloc((size_t)Hout * Wout * Nout);
+    op.rows_per_sample = Hout * Wout;
+    op.flops_per_row = 2.0 * Hout * Wout * (double)w.N * g.K;
+    op.bytes_per_row = ((double)Hin * Win * (C1 + C2) + (double)Hout * Wout * Nout * (residual ? 2 : 1)) * e.elt;
+    op.bytes_fixed = (double)w.N * g.K * e.elt;
+    e.ops.push_back(op);
+    return g.out;
+  }
+  void* gn(const void* s1, int C1, const void* s2, int C2, int HW, float eps, int silu, const float* gamma,
+           const float* beta, float* stats) {
+    Op op{};
+    op.kind = OP_GN;
+    op.cls = PC_GROUP_NORM;
+    GroupNormParams& p = op.gn;
+    p.src1 = s1; p.src2 = s2; p.C1 = C1; p.C2 = C2; p.HW = HW; p.groups = e.cfg.norm_groups;
+    p.eps = eps; p.silu = silu; p.gamma = gamma; p.beta = beta; p.stats = stats;
+    p.out = aalloc((size_t)HW * (C1 + C2));
+    op.rows_per_sample = HW;
+    op.bytes_per_row = 2.0 * HW * (C1 + C2) * e.elt;
+    e.ops.push_back(op);
+    return p.out;
+  }
+  void* ln(const void* src, int rows, int C, const float* gamma, const float* beta) {
+    Op op{};
+    op.kind = OP_LN;
+    op.cls = PC_LAYER_NORM;
+    LayerNormParams& p = op.ln;
+    p.src = src; p.C = C; p.eps = 1e-5f; p.gamma = gamma; p.beta = beta;
+    p.out = aalloc((size_t)rows * C);
+    op.rows_per_sample = rows;
+    op.bytes_per_row = 2.0 * rows * C * e.elt;
+    e.ops.push_back(op);
+    return p.out;
+  }
+  void* attn(const void* q, int ldq, const void* k, const void* v, int ldkv, int Sq, int Skv, int heads, int d,
+             bool cached, size_t cache_stride_elems) {
+    Op op{};
+    op.kind = OP_ATTN;
+    AttnParams& p = op.at;
+    p.q = q; p.k = k; p.v = v; p.ldq = ldq; p.ldk = ldkv; p.ldv = ldkv; p.ldo = heads * d;
+    p.Sq = Sq; p.Skv = Skv; p.heads = heads; p.d = d;
+    p.scale = (float)(1.0 / sqrt((double)d));
+    if (cached) {
+      p.kv_select = (const int*)(e.persist + e.off_sel_zero);  // patched per launch
+      p.kv_select_stride = (long long)cache_stride_elems;
+      p.kv_sample_stride = 0;
+    } else {
+      p.kv_select = nullptr;
+      p.kv_sample_stride = (long long)Skv * ldkv;
+    }
+    p.out = aalloc((size_t)Sq * heads * d);
+    op.mfma = e.use_mfma && attention_mfma_supported(p);
+    op.cls = op.mfma ? PC_ATTN_MFMA : PC_ATTN_VALU;
+    op.rows_per_sample = Sq;
+    op.flops_per_row = 4.0 * Sq * (double)Skv * d * heads;
+    op.bytes_per_row = (2.0 * Sq * heads * d + (cached ? 0.0 : 2.0 * Skv * heads * d)) * e.elt;
+    e.ops.push_back(op);
+    return p.out;
+  }
+
+  // ---- blocks
+  struct ResW {
+    float *g1, *b1, *g2, *b2;
+    LinW c1, c2, skip, temb;
+    bool has_skip;
+    size_t rowbias;  // persist offset, [max_batch][cout] fp32
+  };
+  ResW res_weights(const std::string& p, int c1in, int c2in, int cout) {
+    ResW r;
+    int cin = c1in + c2in;
+    r.g1 = fvec(p + ".norm1.g", cin, 2);
+    r.b1 = fvec(p + ".norm1.b", cin, 3);
+    r.c1 = matw(p + ".conv1", cout, cin, 3, true, true, false, cin, 0);
+    r.temb = f32w(p + ".temb", cout, temb_dim);
+    r.g2 = fvec(p + ".norm2.g", cout, 2);
+    r.b2 = fvec(p + ".norm2.b", cout, 3);
+    r.c2 = matw(p + ".conv2", cout, cout, 3, true, true, false, cout, 0);
+    r.has_skip = cin != cout;
+    if (r.has_skip) r.skip = matw(p + ".skip", cout, cin, 1, true, true, false, c1in, c2in);
+    r.rowbias = palloc((size_t)e.max_batch * cout * 4);
+    return r;
+  }
+
+  float* stats_buf() { return (float*)(e.persist + stats_off); }
+  size_t stats_off = 0;
+
+  // x = concat(x1, x2) (x2 may be null); consumes nothing, returns a new buffer
+  void* res_block(const std::string& name, const void* x1, int c1in, const void* x2, int c2in, int cout, int H, int W) {
+    ResW r = res_weights(name, c1in, c2in, cout);
+    int HW = H * W;
+    // time-embedding bias of this block: Linear(SiLU(temb)) per batch row
+    {
+      Op op{};
+      op.kind = OP_IGEMM;
+      op.cls = PC_IGEMM_VALU;
+      IgemmParams& g = op.g;
+      g.src1 = e.persist + e.off_h2; g.C1 = temb_dim; g.C2 = 0;
+      g.Hin = g.Win = g.Hout = g.Wout = 1; g.ksize = 1; g.stride = 1;
+      g.N = cout; g.K = temb_dim;
+      g.W = e.weights + r.temb.w;
+      g.bias = (const float*)(e.weights + r.temb.b);
+      g.out = e.persist + r.rowbias;
+      g.splitk = 1;
+      op.rows_per_sample = 1;
+      e.temb_ops.push_back(op);
+    }
+    void* t1 = gn(x1, c1in, x2, c2in, HW, 1e-5f, 1, r.g1, r.b1, stats_buf());
+    void* t2 = conv(t1, c1in + c2in, nullptr, 0, H, W, H, W, 3, 1, 0, r.c1, (const float*)(e.persist + r.rowbias), cout,
+                    nullptr, EPI_NONE);
+    afree(t1);
+    void* t3 = gn(t2, cout, nullptr, 0, HW, 1e-5f, 1, r.g2, r.b2, stats_buf());
+    afree(t2);
+    const void* skip = x1;
+    void* sk = nullptr;
+    if (r.has_skip) {
+      sk = conv(x1, c1in, x2, c2in, H, W, H, W, 1, 1, 0, r.skip, nullptr, 0, nullptr, EPI_NONE);
+      skip = sk;
+    }
+    void* out = conv(t3, cout, nullptr, 0, H, W, H, W, 3, 1, 0, r.c2, nullptr, 0, skip, EPI_NONE);
+    afree(t3);
+    if (sk) afree(sk);
+    return out;
+  }
+
+  void* transformer(const std::string& p, void* x, int C, int H, int W) {
+    const int HW = H * W, L = e.cfg.context_len, D = e.cfg.context_dim;
+    const int heads = e.cfg.num_heads > 0 ? e.cfg.num_heads : C / e.cfg.head_dim;
+    const int d = C / heads;
+    float* gng = fvec(p + ".norm.g", C, 2);
+    float* gnb = fvec(p + ".norm.b", C, 3);
+    LinW pin = matw(p + ".proj_in", C, C, 1, false, true, false, C, 0);
+    float* l1g = fvec(p + ".ln1.g", C, 2);
+    float* l1b = fvec(p + ".ln1.b", C, 3);
+    LinW qkv = fused({p + ".attn1.q", p + ".attn1.k", p + ".attn1.v"}, C, C);
+    LinW o1 = matw(p + ".attn1.o", C, C, 1, false, true, false, C, 0);
+    float* l2g = fvec(p + ".ln2.g", C, 2);
+    float* l2b = fvec(p + ".ln2.b", C, 3);
+    LinW q2 = fused({p + ".attn2.q"}, C, C);
+    KVSite site;
+    site.w = fused({p + ".attn2.k", p + ".attn2.v"}, C, D);
+    site.C = C;
+    site.cache = palloc((size_t)2 * L * 2 * C * e.elt);
+    e.kv_sites.push_back(site);
+    LinW o2 = matw(p + ".attn2.o", C, C, 1, false, true, false, C, 0);
+    float* l3g = fvec(p + ".ln3.g", C, 2);
+    float* l3b = fvec(p + ".ln3.b", C, 3);
+    LinW ffi = matw(p + ".ff.in", 8 * C, C, 1, false, true, true, C, 0);
+    LinW ffo = matw(p + ".ff.out", C, 4 * C, 1, false, true, false, 4 * C, 0);
+    LinW pout = matw(p + ".proj_out", C, C, 1, false, true, false, C, 0);
+
+    void* t = gn(x, C, nullptr, 0, HW, 1e-6f, 0, gng, gnb, stats_buf());
+    void* h = conv(t, C, nullptr, 0, H, W, H, W, 1, 1, 0, pin, nullptr, 0, nullptr, EPI_NONE);
+    afree(t);
+    // self-attention
+    void* n1 = ln(h, HW, C, l1g, l1b);
+    void* qk = conv(n1, C, nullptr, 0, H, W, H, W, 1, 1, 0, qkv, nullptr, 0, nullptr, EPI_NONE);
+    afree(n1);
+    char* qkb = (char*)qk;
+    void* a1 = attn(qkb, 3 * C, qkb + (size_t)C * e.elt, qkb + (size_t)2 * C * e.elt, 3 * C, HW, HW, heads, d, false, 0);
+    afree(qk);
+    void* h2 = conv(a1, C, nullptr, 0, H, W, H, W, 1, 1, 0, o1, nullptr, 0, h, EPI_NONE);
+    afree(a1);
+    afree(h);
+    // cross-attention with the cached K/V of the prompt
+    void* n2 = ln(h2, HW, C, l2g, l2b);
+    void* qc = conv(n2, C, nullptr, 0, H, W, H, W, 1, 1, 0, q2, nullptr, 0, nullptr, EPI_NONE);
+    afree(n2);
+    char* cache = e.persist + site.cache;
+    void* a2 = attn(qc, C, cache, cache + (size_t)C * e.elt, 2 * C, HW, L, heads, d, true, (size_t)L * 2 * C);
+    afree(qc);
+    void* h3 = conv(a2, C, nullptr, 0, H, W, H, W, 1, 1, 0, o2, nullptr, 0, h2, EPI_NONE);
+    afree(a2);
+    afree(h2);
+    // GEGLU feed-forward
+    void* n3 = ln(h3, HW, C, l3g, l3b);
+    void* u = conv(n3, C, nullptr, 0, H, W, H, W, 1, 1, 0, ffi, nullptr, 0, nullptr, EPI_GEGLU);
+    afree(n3);
+    void* h4 = conv(u, 4 * C, nullptr, 0, H, W, H, W, 1, 1, 0, ffo, nullptr, 0, h3, EPI_NONE);
+    afree(u);
+    afree(h3);
+    void* out = conv(h4, C, nullptr, 0, H, W, H, W, 1, 1, 0, pout, nullptr, 0, x, EPI_NONE);
+    afree(h4);
+    return out;
+  }
+
+  void build() {
+    const sdstream_config& c = e.cfg;
+    const int nl = c.n_levels, c0 = c.block_channels[0];
+    int H = c.latent_h, W = c.latent_w;
+    e.ops.clear();
+    e.temb_ops.clear();
+    e.kv_sites.clear();
+    e.act = PlanAllocator();
+
+    // persistent small buffers
+    e.off_tdev = palloc((size_t)e.max_batch * 4);
+    e.off_emb = palloc((size_t)e.max_batch * c0 * 4);
+    e.off_h1 = palloc((size_t)e.max_batch * temb_dim * 4);
+    e.off_h2 = palloc((size_t)e.max_batch * temb_dim * 4);
+    e.off_ctxT = palloc((size_t)2 * c.context_len * c.context_dim * e.elt);
+    e.off_sel_zero = palloc((size_t)e.max_batch * 4);
+    e.off_sel_step = palloc((size_t)e.max_batch * 4);
+    stats_off = palloc((size_t)e.max_batch * c.norm_groups * 2 * 4);
+    const size_t rows_state = (size_t)c.n_streams * c.n_denoise;
+    for (int i = 0; i < 2; ++i) {
+      e.off_x[i] = palloc((size_t)e.max_batch * e.E * 4);
+      e.off_r[i] = palloc(rows_state * e.E * 4);
+    }
+    e.off_eps = palloc((size_t)e.max_batch * e.E * 4);
+    e.off_noise = palloc(rows_state * e.E * 4);
+    e.off_ab = palloc((size_t)2 * c.n_denoise * 4);
+    e.off_unet_x = palloc((size_t)e.max_batch * e.E * 4);
+
+    // time embedding MLP (float32)
+    LinW t1 = f32w("time.lin1", temb_dim, c0);
+    LinW t2 = f32w("time.lin2", temb_dim, temb_dim);
+    for (int j = 0; j < 2; ++j) {
+      Op op{};
+      op.kind = OP_IGEMM;
+      op.cls = PC_IGEMM_VALU;
+      IgemmParams& g = op.g;
+      g.src1 = e.persist + (j == 0 ? e.off_emb : e.off_h1);
+      g.C1 = j == 0 ? c0 : temb_dim;
+      g.Hin = g.Win = g.Hout = g.Wout = 1; g.ksize = 1; g.stride = 1;
+      g.N = temb_dim; g.K = g.C1;
+      const LinW& w = j == 0 ? t1 : t2;
+      g.W = e.weights + w.w;
+      g.bias = (const float*)(e.weights + w.b);
+      g.out = e.persist + (j == 0 ? e.off_h1 : e.off_h2);
+      g.epilogue = EPI_SILU;  // every consumer of temb applies SiLU first
+      g.splitk = 1;
+      op.rows_per_sample = 1;
+      e.temb_ops.push_back(op);
+    }
+
+    // conv_in (fp32 weights, canonical OIHW)
+    size_t ciw = walloc((size_t)c0 * c.in_channels * 9 * 4);
+    add_entry("conv_in.w", {c0, c.in_channels, 3, 3}, 0, LA_F32, ciw, c0, c.in_channels, 9, 0);
+    float* cib = fvec("conv_in.b", c0, 1);
+    void* h;
+    {
+      Op op{};
+      op.kind = OP_CONV_IN;
+      op.cls = PC_CONV_IN;
+      op.cw_f32 = (const float*)(e.weights + ciw);
+      op.cb = cib;
+      op.cout_ = aalloc((size_t)H * W * c0);
+      op.rows_per_sample = H * W;
+      op.flops_per_row = 2.0 * H * W * c0 * c.in_channels * 9;
+      op.bytes_per_row = (double)H * W * (c.in_channels * 4 + c0 * e.elt);
+      e.ops.push_back(op);
+      h = op.cout_;
+    }
+    std::vector<std::pair<void*, int>> skips;
+    skips.push_back({h, c0});
+    int ch = c0;
+    for (int l = 0; l < nl; ++l) {
+      const int cl = c.block_channels[l];
+      const bool at = (c.attn_level_mask >> l) & 1;
+      for (int j = 0; j < c.layers_per_block; ++j) {
+        std::string p = "down." + std::to_string(l);
+        void* r = res_block(p + ".res." + std::to_string(j), h, ch, nullptr, 0, cl, H, W);
+        ch = cl;
+        if (at) {
+          void* t = transformer(p + ".attn." + std::to_string(j), r, ch, H, W);
+          afree(r);
+          r = t;
+        }
+        h = r;
+        skips.push_back({h, ch});
+      }
+      if (l != nl - 1) {
+        LinW dw = matw("down." + std::to_string(l) + ".downsample", ch, ch, 3, true, true, false, ch, 0);
+        int Ho = (H - 1) / 2 + 1, Wo = (W - 1) / 2 + 1;
+        h = conv(h, ch, nullptr, 0, H, W, Ho, Wo, 3, 2, 0, dw, nullptr, 0, nullptr, EPI_NONE);
+        H = Ho; W = Wo;
+        skips.push_back({h, ch});
+      }
+    }
+    {
+      void* r = res_block("mid.res.0", h, ch, nullptr, 0, ch, H, W);
+      if (c.mid_attention) {
+        void* t = transformer("mid.attn", r, ch, H, W);
+        afree(r);
+        r = t;
+      }
+      h = res_block("mid.res.1", r, ch, nullptr, 0, ch, H, W);
+      afree(r);
+    }
+    // (the last skip entry is the tensor the middle block started from; it is still needed by the up path)
+    bool h_owned = true;
+    for (int l = nl - 1; l >= 0; --l) {
+      const int cl = c.block_channels[l];
+      const bool at = (c.attn_level_mask >> l) & 1;
+      for (int j = 0; j < c.layers_per_block + 1; ++j) {
+        std::string p = "up." + std::to_string(l);
+        auto sk = skips.back();
+        skips.pop_back();
+        void* r = res_block(p + ".res." + std::to_string(j), h, ch, sk.first, sk.second, cl, H, W);
+        if (h_owned) afree(h);
+        afree(sk.first);
+        ch = cl;
+        if (at) {
+          void* t = transformer(p + ".attn." + std::to_string(j), r, ch, H, W);
+          afree(r);
+          r = t;
+        }
+        h = r;
+        h_owned = true;
+      }
+      if (l != 0) {
+        LinW uw = matw("up." + std::to_string(l) + ".upsample", ch, ch, 3, true, true, false, ch, 0);
+        void* u = conv(h, ch, nullptr, 0, H, W, 2 * H, 2 * W, 3, 1, 1, uw, nullptr, 0, nullptr, EPI_NONE);
+        afree(h);
+        h = u;
+        H *= 2; W *= 2;
+      }
+    }
+    float* og = fvec("out.norm.g", ch, 2);
+    float* ob = fvec("out.norm.b", ch, 3);
+    void* t = gn(h, ch, nullptr, 0, H * W, 1e-5f, 1, og, ob, stats_buf());
+    afree(h);
+    // conv_out: T [Cout][9][C0]
+    size_t cow = walloc((size_t)c.in_channels * 9 * ch * e.elt);
+    add_entry("conv_out.w", {c.in_channels, ch, 3, 3}, 0, LA_ROWMAJOR, cow, c.in_channels, ch, 9, 0);
+    float* cob = fvec("conv_out.b", c.in_channels, 1);
+    {
+      Op op{};
+      op.kind = OP_CONV_OUT;
+      op.cls = PC_CONV_OUT;
+      op.cin = t;
+      op.cw = e.weights + cow;
+      op.cb = cob;
+      op.rows_per_sample = H * W;
+      op.flops_per_row = 2.0 * H * W * c.in_channels * ch * 9;
+      op.bytes_per_row = (double)H * W * (c.in_channels * 4 + ch * e.elt);
+      e.ops.push_back(op);
+    }
+    afree(t);
+    e.flops_per_row = 0;
+    for (const Op& op : e.ops) e.flops_per_row += op.flops_per_row;
+  }
+};
+
+int validate(const sdstream_config& c, std::string& why) {
+  char buf[256];
+#define BAD(...) do { snprintf(buf, sizeof buf, __VA_ARGS__); why = buf; return SDSTREAM_E_INVALID_ARG; } while (0)
+  if (c.in_channels < 1 || c.in_channels > 64) BAD("in_channels %d out of range", c.in_channels);
+  if (c.n_levels < 1 || c.n_levels > SDSTREAM_MAX_LEVELS) BAD("n_levels %d out of range", c.n_levels);
+  if (c.layers_per_block < 1 || c.layers_per_block > 8) BAD("layers_per_block %d out of range", c.layers_per_block);
+  if (c.norm_groups < 1) BAD("norm_groups %d", c.norm_groups);
+  if ((c.num_heads > 0) == (c.head_dim > 0)) BAD("exactly one of num_heads / head_dim must be positive");
+  if (c.context_len < 1 || c.context_dim < 1) BAD("context %dx%d", c.context_len, c.context_dim);
+  if (c.latent_h < 1 || c.latent_w < 1) BAD("latent %dx%d", c.latent_h, c.latent_w);
+  if (c.latent_h % (1 << (c.n_levels - 1)) || c.latent_w % (1 << (c.n_levels - 1)))
+    BAD("latent %dx%d must be divisible by 2^(n_levels-1)", c.latent_h, c.latent_w);
+  if (c.dtype != 0 && c.dtype != 1) BAD("dtype %d", c.dtype);
+  if (c.n_denoise < 1 || c.n_denoise > 64) BAD("n_denoise %d out of range", c.n_denoise);
+  if (c.n_streams < 1 || c.n_streams > 64) BAD("n_streams %d out of range", c.n_streams);
+  if (c.cfg_mode < 0 || c.cfg_mode > 3) BAD("cfg_mode %d", c.cfg_mode);
+  if (c.scheduler < 0 || c.scheduler > 1) BAD("scheduler %d", c.scheduler);
+  for (int l = 0; l < c.n_levels; ++l) {
+    int ch = c.block_channels[l];
+    if (ch < 1 || ch % c.norm_groups) BAD("block_channels[%d]=%d not a multiple of norm_groups", l, ch);
+    if (l == 0 && ch % 2) BAD("block_channels[0] must be even");
+    bool at = ((c.attn_level_mask >> l) & 1) || (l == c.n_levels - 1 && c.mid_attention);
+    if (at) {
+      int heads = c.num_heads > 0 ? c.num_heads : ch / c.head_dim;
+      if (heads < 1 || ch % heads) BAD("level %d: %d channels do not split into heads", l, ch);
+      int d = ch / heads;
+      if (d % 4 || d > 160) BAD("level %d: head width %d must be a multiple of 4 and at most 160", l, d);
+    }
+  }
+  // skip concats must also split into groups
+  return SDSTREAM_OK;
+#undef BAD
+}
+
+void default_schedule(double* alphas) {
+  // scaled-linear: beta_t = (linspace(sqrt(.00085), sqrt(.012), 1000))^2, alpha = cumulative product of 1 - beta
+  double s0 = sqrt(0.00085), s1 = sqrt(0.012), prod = 1.0;
+  for (int t = 0; t < 1000; ++t) {
+    double sb = s0 + (s1 - s0) * (double)t / 999.0;
+    prod *= 1.0 - sb * sb;
+    alphas[t] = prod;
+  }
+}
+
+int rows_for_mode(const sdstream_config& c) {
+  int base = c.n_streams * c.n_denoise;
+  if (c.cfg_mode == SDSTREAM_CFG_FULL) return 2 * base;
+  if (c.cfg_mode == SDSTREAM_CFG_ONETIME) return base + c.n_streams;
+  return base;
+}
+
+void reset_state(sdstream* h) {
+  h->cur = 0;
+  h->calls = 0;
+  h->ssf_ref = -1;
+  h->ssf_ref_norm = 0;
+}
+
+// ------------------------------------------------------------------------------------------------
+// launching
+// ------------------------------------------------------------------------------------------------
+void launch_op(sdstream* h, const Op& op0, int N, const int* kv_select, hipStream_t s) {
+  const bool bf = h->cfg.dtype == 1;
+  switch (op0.kind) {
+    case OP_IGEMM: {
+      IgemmParams g = op0.g;
+      g.M = N * op0.rows_per_sample;
+      if (op0.mfma) launch_igemm_mfma(g, s);
+      else if (bf) launch_igemm_generic<bf16_t>(g, s);
+      else launch_igemm_generic<float>(g, s);
+      break;
+    }
+    case OP_GN: {
+      GroupNormParams p = op0.gn;
+      p.samples = N;
+      if (bf) launch_group_norm<bf16_t>(p, s); else launch_group_norm<float>(p, s);
+      break;
+    }
+    case OP_LN: {
+      LayerNormParams p = op0.ln;
+      p.rows = N * op0.rows_per_sample;
+      if (bf) launch_layer_norm<bf16_t>(p, s); else launch_layer_norm<float>(p, s);
+      break;
+    }
+    case OP_ATTN: {
+      AttnParams p = op0.at;
+      p.samples = N;
+      if (p.kv_select) p.kv_select = kv_select;
+      if (op0.mfma) launch_attention_mfma(p, s);
+      else if (bf) launch_attention_generic<bf16_t>(p, s);
+      else launch_attention_generic<float>(p, s);
+      break;
+    }
+    case OP_CONV_IN: {
+      const sdstream_config& c = h->cfg;
+      const float* x = (const float*)op0.cin;
+      if (bf) launch_conv_in<bf16_t>(x, op0.cw_f32, op0.cb, op0.cout_, N, c.in_channels, c.latent_h, c.latent_w, c.block_channels[0], s);
+      else launch_conv_in<float>(x, op0.cw_f32, op0.cb, op0.cout_, N, c.in_channels, c.latent_h, c.latent_w, c.block_channels[0], s);
+      break;
+    }
+    case OP_CONV_OUT: {
+      const sdstream_config& c = h->cfg;
+      float* out = (float*)op0.cout_;
+      if (bf) launch_conv_out<bf16_t>(op0.cin, op0.cw, op0.cb, out, N, c.in_channels, c.latent_h, c.latent_w, c.block_channels[0], s);
+      else launch_conv_out<float>(op0.cin, op0.cw, op0.cb, out, N, c.in_channels, c.latent_h, c.latent_w, c.block_channels[0], s);
+      break;
+    }
+  }
+}
+
+int prof_begin(sdstream* h, int cls, double flops, double bytes, hipStream_t s) {
+  sdstream::ProfRec r;
+  r.cls = cls; r.flops = flops; r.bytes = bytes;
+  HIP_TRY(h, hipEventCreate(&r.a));
+  HIP_TRY(h, hipEventCreate(&r.b));
+  HIP_TRY(h, hipEventRecord(r.a, s));
+  h->prof_pending.push_back(r);
+  return SDSTREAM_OK;
+}
+int prof_end(sdstream* h, hipStream_t s) {
+  HIP_TRY(h, hipEventRecord(h->prof_pending.back().b, s));
+  return SDSTREAM_OK;
+}
+
+// the U-Net on `N` rows: x (fp32 NCHW, device) -> eps (fp32 NCHW, device)
+int run_unet(sdstream* h, const float* x, float* eps, int N, const int* kv_select, bool for_step, hipStream_t s) {
+  const bool graph = h->graph_enabled && !h->profiling && for_step;
+  // the first and last op read / write caller-visible buffers
+  h->ops.front().cin = x;
+  h->ops.back().cout_ = eps;
+  if (graph) {
+    const int key = N * 2 + h->cur;  // the input batch alternates between two buffers
+    auto it = h->graphs.find(key);
+    if (it == h->graphs.end()) {
+      if (!h->cap_stream) HIP_TRY(h, hipStreamCreateWithFlags(&h->cap_stream, hipStreamNonBlocking));
+      HIP_TRY(h, hipStreamBeginCapture(h->cap_stream, hipStreamCaptureModeThreadLocal));
+      for (const Op& op : h->ops) launch_op(h, op, N, kv_select, h->cap_stream);
+      hipGraph_t gph = nullptr;
+      HIP_TRY(h, hipStreamEndCapture(h->cap_stream, &gph));
+      hipGraphExec_t ex = nullptr;
+      hipError_t er = hipGraphInstantiate(&ex, gph, nullptr, nullptr, 0);
+      hipGraphDestroy(gph);
+      if (er != hipSuccess) return fail(h, SDSTREAM_E_HIP, "hipGraphInstantiate: %s", hipGetErrorString(er));
+      it = h->graphs.emplace(key, ex).first;
+    }
+    HIP_TRY(h, hipGraphLaunch(it->second, s));
+  } else {
+    for (const Op& op : h->ops) {
+      if (h->profiling) {
+        int rc = prof_begin(h, op.cls, op.flops_per_row * N, op.bytes_per_row * N + op.bytes_fixed, s);
+        if (rc) return rc;
+      }
+      launch_op(h, op, N, kv_select, s);
+      if (h->profiling) {
+        int rc = prof_end(h, s);
+        if (rc) return rc;
+      }
+    }
+  }
+  HIP_TRY(h, hipGetLastError());
+  return SDSTREAM_OK;
+}
+
+// time-embedding biases for the rows' timesteps (cached)
+int ensure_temb(sdstream* h, const std::vector<int>& t, hipStream_t s) {
+  if (t == h->temb_cached) return SDSTREAM_OK;
+  const int N = (int)t.size();
+  // rare path (timesteps changed): drain the stream, then a blocking upload
+  HIP_TRY(h, hipStreamSynchronize(s));
+  HIP_TRY(h, hipMemcpy(h->persist + h->off_tdev, t.data(), (size_t)N * 4, hipMemcpyHostToDevice));
+  launch_time_embedding((const int*)(h->persist + h->off_tdev), (float*)(h->persist + h->off_emb), N,
+                        h->cfg.block_channels[0], s);
+  for (const Op& op : h->temb_ops) {
+    IgemmParams g = op.g;
+    g.M = N;
+    launch_igemm_generic<float>(g, s);
+  }
+  HIP_TRY(h, hipGetLastError());
+  h->temb_cached = t;
+  return SDSTREAM_OK;
+}
+
+// K/V of the prompt for every cross-attention site; slot 0 positive, slot 1 negative
+int build_kv(sdstream* h, const float* ctx, const float* neg, hipStream_t s) {
+  const sdstream_config& c = h->cfg;
+  const bool bf = c.dtype == 1;
+  const long long n = (long long)c.context_len * c.context_dim;
+  char* ctxT = h->persist + h->off_ctxT;
+  for (int slot = 0; slot < 2; ++slot) {
+    const float* src = slot == 0 ? ctx : neg;
+    if (!src) continue;
+    void* dst = ctxT + (size_t)slot * n * h->elt;
+    if (bf) launch_convert<bf16_t>(src, dst, n, s); else launch_convert<float>(src, dst, n, s);
+    for (const KVSite& site : h->kv_sites) {
+      IgemmParams g{};
+      g.src1 = dst; g.C1 = c.context_dim; g.C2 = 0;
+      g.Hin = c.context_len; g.Win = 1; g.Hout = c.context_len; g.Wout = 1;
+      g.ksize = 1; g.stride = 1;
+      g.M = c.context_len; g.N = 2 * site.C; g.K = c.context_dim;
+      g.W = h->weights + site.w.w;
+      g.out = h->persist + site.cache + (size_t)slot * c.context_len * 2 * site.C * h->elt;
+      g.splitk = 1;
+      if (site.w.mfma) launch_igemm_mfma(g, s);
+      else if (bf) launch_igemm_generic<bf16_t>(g, s);
+      else launch_igemm_generic<float>(g, s);
+    }
+  }
+  HIP_TRY(h, hipGetLastError());
+  return SDSTREAM_OK;
+}
+
+uint64_t splitmix64_mix(uint64_t z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+  return z ^ (z >> 31);
+}
+
+}  // namespace
+
+// ================================================================================================
+// C ABI
+// ================================================================================================
+extern "C" {
+
+const char* sdstream_last_error(const sdstream_t* h) { return h ? h->err.c_str() : g_create_error.c_str(); }
+
+int sdstream_create(const sdstream_config* cfg, sdstream_t** out) {
+  if (!cfg || !out) return fail(nullptr, SDSTREAM_E_INVALID_ARG, "null argument");
+  *out = nullptr;
+  std::string why;
+  int rc = validate(*cfg, why);
+  if (rc) return fail(nullptr, rc, "%s", why.c_str());
+  sdstream* h = new (std::nothrow) sdstream();
+  if (!h) return fail(nullptr, SDSTREAM_E_NOMEM, "out of host memory");
+  h->cfg = *cfg;
+  h->elt = cfg->dtype == 1 ? 2 : 4;
+  h->use_mfma = cfg->dtype == 1 && getenv("SDSTREAM_NO_MFMA") == nullptr;
+  h->E = cfg->in_channels * cfg->latent_h * cfg->latent_w;
+  h->max_batch = rows_for_mode(*cfg);
+  memset(h->prof, 0, sizeof h->prof);
+  default_schedule(h->alphas);
+  // pass 1: sizes and manifest
+  {
+    Builder b(*h, true);
+    b.build();
+    h->weight_bytes = b.wbytes;
+    h->persist_bytes = b.pbytes;
+    h->act_bytes = h->act.peak * (size_t)h->max_batch;
+  }
+  h->n_params = 0;
+  for (const Entry& en : h->manifest) h->n_params += (int64_t)en.count;
+  hipError_t e1 = hipMalloc((void**)&h->weights, h->weight_bytes);
+  hipError_t e2 = e1 == hipSuccess ? hipMalloc((void**)&h->persist, h->persist_bytes) : e1;
+  hipError_t e3 = e2 == hipSuccess ? hipMalloc((void**)&h->act_base, h->act_bytes ? h->act_bytes : 256) : e2;
+  if (e3 != hipSuccess) {
+    int code = fail(nullptr, e3 == hipErrorOutOfMemory ? SDSTREAM_E_NOMEM : SDSTREAM_E_HIP, "hipMalloc: %s",
+                    hipGetErrorString(e3));
+    sdstream_destroy(h);
+    return code;
+  }
+  if (hipMemset(h->persist, 0, h->persist_bytes) != hipSuccess) {
+    sdstream_destroy(h);
+    return fail(nullptr, SDSTREAM_E_HIP, "hipMemset failed");
+  }
+  // pass 2: real pointers
+  {
+    Builder b(*h, false);
+    b.build();
+  }
+  reset_state(h);
+  *out = h;
+  return SDSTREAM_OK;
+}
+
+void sdstream_destroy(sdstream_t* h) {
+  if (!h) return;
+  hipDeviceSynchronize();
+  for (auto& kv : h->graphs) hipGraphExecDestroy(kv.second);
+  if (h->cap_stream) hipStreamDestroy(h->cap_stream);
+  for (auto& r : h->prof_pending) { hipEventDestroy(r.a); hipEventDestroy(r.b); }
+  if (h->weights) hipFree(h->weights);
+  if (h->persist) hipFree(h->persist);
+  if (h->act_base) hipFree(h->act_base);
+  for (int i = 0; i < 2; ++i) if (h->ssf_buf[i]) hipFree(h->ssf_buf[i]);
+  if (h->ssf_sums) hipFree(h->ssf_sums);
+  if (h->ssf_host) hipHostFree(h->ssf_host);
+  delete h;
+}
+
+int64_t sdstream_param_count(const sdstream_t* h) { return h ? h->n_params : 0; }
+int32_t sdstream_manifest_size(const sdstream_t* h) { return h ? (int32_t)h->manifest.size() : 0; }
+int32_t sdstream_max_batch(const sdstream_t* h) { return h ? h->max_batch : 0; }
+double sdstream_flops_per_row(const sdstream_t* h) { return h ? h->flops_per_row : 0.0; }
+
+int sdstream_manifest_entry(const sdstream_t* h, int32_t index, char* name, size_t name_cap, int32_t shape[4],
+                            int32_t* ndim, int32_t* kind) {
+  if (!h) return SDSTREAM_E_INVALID_ARG;
+  sdstream* hm = const_cast<sdstream*>(h);
+  if (index < 0 || index >= (int32_t)h->manifest.size()) return fail(hm, SDSTREAM_E_INVALID_ARG, "index out of range");
+  const Entry& en = h->manifest[index];
+  if (name && name_cap) {
+    strncpy(name, en.name.c_str(), name_cap - 1);
+    name[name_cap - 1] = 0;
+  }
+  if (shape) for (int i = 0; i < 4; ++i) shape[i] = en.shape[i];
+  if (ndim) *ndim = en.ndim;
+  if (kind) *kind = en.kind;
+  return SDSTREAM_OK;
+}
+
+int sdstream_load_weights(sdstream_t* h, const void* host_blob, size_t bytes) {
+  if (!h || !host_blob) return h ? fail(h, SDSTREAM_E_INVALID_ARG, "null blob") : SDSTREAM_E_INVALID_ARG;
+  if (bytes != (size_t)h->n_params * 4)
+    return fail(h, SDSTREAM_E_SHAPE, "blob has %zu bytes, the manifest needs %zu", bytes, (size_t)h->n_params * 4);
+  size_t max_count = 0;
+  for (const Entry& en : h->manifest) max_count = en.count > max_count ? en.count : max_count;
+  float* stage = nullptr;
+  HIP_TRY(h, hipMalloc((void**)&stage, max_count * 4));
+  const bool bf = h->cfg.dtype == 1;
+  const float* src = (const float*)host_blob;
+  hipStream_t s = nullptr;
+  int rc = SDSTREAM_OK;
+  for (const Entry& en : h->manifest) {
+    hipError_t er = hipMemcpy(stage, src, en.count * 4, hipMemcpyHostToDevice);
+    if (er != hipSuccess) { rc = fail(h, SDSTREAM_E_HIP, "hipMemcpy: %s", hipGetErrorString(er)); break; }
+    src += en.count;
+    void* dst = h->weights + en.dst_off;
+    switch (en.action) {
+      case LA_F32: launch_copy_rows_f32(stage, (float*)dst, (long long)en.count, s); break;
+      case LA_ROWMAJOR:
+        if (bf) launch_repack_rowmajor<bf16_t>(stage, dst, en.O, en.I, en.taps, en.geglu, s);
+        else launch_repack_rowmajor<float>(stage, dst, en.O, en.I, en.taps, en.geglu, s);
+        break;
+      case LA_MFMA: launch_repack_mfma(stage, dst, en.O, en.I, en.taps, en.geglu, s); break;
+      case LA_BIAS_PERM: launch_permute_bias(stage, (float*)dst, en.O, en.geglu, s); break;
+    }
+    er = hipDeviceSynchronize();
+    if (er != hipSuccess) { rc = fail(h, SDSTREAM_E_HIP, "repack: %s", hipGetErrorString(er)); break; }
+  }
+  hipFree(stage);
+  if (rc) return rc;
+  h->weights_loaded = true;
+  h->temb_cached.clear();
+  h->kv_valid = false;
+  return SDSTREAM_OK;
+}
+
+int sdstream_set_schedule(sdstream_t* h, const float* alphas_cumprod) {
+  if (!h) return SDSTREAM_E_INVALID_ARG;
+  if (alphas_cumprod) {
+    for (int t = 0; t < 1000; ++t)
+      if (!(alphas_cumprod[t] > 0.f && alphas_cumprod[t] <= 1.f))
+        return fail(h, SDSTREAM_E_INVALID_ARG, "alphas_cumprod[%d] = %g not in (0,1]", t, (double)alphas_cumprod[t]);
+    for (int t = 0; t < 1000; ++t) h->alphas[t] = alphas_cumprod[t];
+  } else {
+    default_schedule(h->alphas);
+  }
+  h->timesteps.clear();
+  reset_state(h);
+  return SDSTREAM_OK;
+}
+
+int sdstream_set_noise(sdstream_t* h, const float* host_noise) {
+  if (!h || !host_noise) return h ? fail(h, SDSTREAM_E_INVALID_ARG, "null noise") : SDSTREAM_E_INVALID_ARG;
+  size_t bytes = (size_t)h->cfg.n_denoise * h->cfg.n_streams * h->E * 4;
+  HIP_TRY(h, hipMemcpy(h->persist + h->off_noise, host_noise, bytes, hipMemcpyHostToDevice));
+  h->have_noise = true;
+  reset_state(h);
+  return SDSTREAM_OK;
+}
+
+int sdstream_reset(sdstream_t* h) {
+  if (!h) return SDSTREAM_E_INVALID_ARG;
+  HIP_TRY(h, hipDeviceSynchronize());
+  for (int i = 0; i < 2; ++i) {
+    HIP_TRY(h, hipMemset(h->persist + h->off_x[i], 0, (size_t)h->max_batch * h->E * 4));
+    HIP_TRY(h, hipMemset(h->persist + h->off_r[i], 0, (size_t)h->cfg.n_streams * h->cfg.n_denoise * h->E * 4));
+  }
+  reset_state(h);
+  return SDSTREAM_OK;
+}
+
+int sdstream_unet_forward(sdstream_t* h, const float* x, const int32_t* t, const float* ctx, int32_t n, float* eps_out,
+                          void* hip_stream) {
+  if (!h) return SDSTREAM_E_INVALID_ARG;
+  if (!x || !t || !ctx || !eps_out) return fail(h, SDSTREAM_E_INVALID_ARG, "null argument");
+  if (!h->weights_loaded) return fail(h, SDSTREAM_E_NOT_READY, "weights not loaded");
+  if (n < 1 || n > h->max_batch) return fail(h, SDSTREAM_E_SHAPE, "batch %d outside [1,%d]", n, h->max_batch);
+  std::vector<int> tv(t, t + n);
+  for (int v : tv) if (v < 0 || v > 999) return fail(h, SDSTREAM_E_INVALID_ARG, "timestep %d outside [0,999]", v);
+  hipStream_t s = (hipStream_t)hip_stream;
+  int rc = ensure_temb(h, tv, s);
+  if (rc) return rc;
+  rc = build_kv(h, ctx, nullptr, s);
+  if (rc) return rc;
+  h->kv_valid = false;  // the step path must rebuild its own
+  return run_unet(h, x, eps_out, n, (const int*)(h->persist + h->off_sel_zero), false, s);
+}
+
+int sdstream_step(sdstream_t* h, const float* x0_in, const float* context, const float* neg_context,
+                  uint64_t context_epoch, const int32_t* timesteps, float gamma, float delta, float* out_latent,
+                  int32_t* out_valid, void* hip_stream) {
+  if (!h) return SDSTREAM_E_INVALID_ARG;
+  const sdstream_config& c = h->cfg;
+  if (!x0_in || !context || !timesteps || !out_latent) return fail(h, SDSTREAM_E_INVALID_ARG, "null argument");
+  if (!h->weights_loaded) return fail(h, SDSTREAM_E_NOT_READY, "weights not loaded");
+  if (!h->have_noise) return fail(h, SDSTREAM_E_NOT_READY, "noise cache not set");
+  const bool need_neg = c.cfg_mode == SDSTREAM_CFG_FULL || c.cfg_mode == SDSTREAM_CFG_ONETIME;
+  if (need_neg && !neg_context) return fail(h, SDSTREAM_E_INVALID_ARG, "this cfg_mode needs neg_context");
+  const int n = c.n_denoise, S = c.n_streams;
+  for (int i = 0; i < n; ++i) {
+    if (timesteps[i] < 0 || timesteps[i] > 999)
+      return fail(h, SDSTREAM_E_INVALID_ARG, "timestep %d outside [0,999]", timesteps[i]);
+    if (i && timesteps[i] >= timesteps[i - 1]) return fail(h, SDSTREAM_E_INVALID_ARG, "timesteps must strictly decrease");
+  }
+  hipStream_t s = (hipStream_t)hip_stream;
+  std::vector<int> ts(timesteps, timesteps + n);
+  const int rows = h->max_batch;
+  if (ts != h->timesteps) {
+    // new schedule points: constants, selection table, and a fresh queue
+    std::vector<float> ab(2 * n);
+    for (int i = 0; i < n; ++i) {
+      ab[i] = (float)sqrt(h->alphas[ts[i]]);
+      ab[n + i] = (float)sqrt(1.0 - h->alphas[ts[i]]);
+    }
+    std::vector<int> sel(rows, 0);
+    for (int r = S * n; r < rows; ++r) sel[r] = 1;
+    HIP_TRY(h, hipStreamSynchronize(s));
+    HIP_TRY(h, hipMemcpy(h->persist + h->off_ab, ab.data(), ab.size() * 4, hipMemcpyHostToDevice));
+    HIP_TRY(h, hipMemcpy(h->persist + h->off_sel_step, sel.data(), sel.size() * 4, hipMemcpyHostToDevice));
+    int rc = sdstream_reset(h);
+    if (rc) return rc;
+    h->timesteps = ts;
+  }
+  std::vector<int> trow(rows);
+  for (int r = 0; r < S * n; ++r) trow[r] = ts[r % n];
+  for (int r = S * n; r < rows; ++r) trow[r] = c.cfg_mode == SDSTREAM_CFG_FULL ? ts[(r - S * n) % n] : ts[0];
+  int rc = ensure_temb(h, trow, s);
+  if (rc) return rc;
+  if (!h->kv_valid || h->kv_epoch != context_epoch) {
+    rc = build_kv(h, context, need_neg ? neg_context : nullptr, s);
+    if (rc) return rc;
+    h->kv_valid = true;
+    h->kv_epoch = context_epoch;
+  }
+
+  StreamParams p;
+  p.S = S; p.n = n; p.E = h->E; p.mode = c.cfg_mode; p.scheduler = c.scheduler;
+  p.gamma = gamma; p.delta = delta;
+  p.a = (const float*)(h->persist + h->off_ab);
+  p.b = p.a + n;
+  p.noise = (const float*)(h->persist + h->off_noise);
+  p.x0_in = x0_in;
+  p.xcur = (float*)(h->persist + h->off_x[h->cur]);
+  p.xnext = (float*)(h->persist + h->off_x[h->cur ^ 1]);
+  p.rcur = (float*)(h->persist + h->off_r[h->cur]);
+  p.rnext = (float*)(h->persist + h->off_r[h->cur ^ 1]);
+  p.eps = (const float*)(h->persist + h->off_eps);
+  p.out = out_latent;
+
+  const double head_bytes = (double)S * h->E * 4 * 3, tail_bytes = (double)S * n * h->E * 4 * 5;
+  if (h->profiling) { rc = prof_begin(h, PC_STREAM_HEAD, 0, head_bytes, s); if (rc) return rc; }
+  launch_stream_head(p, s);
+  if (h->profiling) { rc = prof_end(h, s); if (rc) return rc; }
+  rc = run_unet(h, p.xcur, (float*)(h->persist + h->off_eps), rows, (const int*)(h->persist + h->off_sel_step), true, s);
+  if (rc) return rc;
+  if (h->profiling) { rc = prof_begin(h, PC_STREAM_TAIL, 0, tail_bytes, s); if (rc) return rc; }
+  launch_stream_tail(p, s);
+  if (h->profiling) { rc = prof_end(h, s); if (rc) return rc; }
+  HIP_TRY(h, hipGetLastError());
+  if (out_valid) *out_valid = h->calls >= n - 1 ? 1 : 0;
+  h->calls++;
+  h->cur ^= 1;
+  return SDSTREAM_OK;
+}
+
+int sdstream_ssf_decide(uint64_t dot, uint64_t n_t, uint64_t n_ref, double eta, uint64_t seed, uint64_t frame_index,
+                        double* prob) {
+  double p = 0.0;
+  if (n_t != 0 && n_ref != 0 && eta < 1.0) {
+    double sc = (double)dot / sqrt((double)n_t * (double)n_ref);
+    if (sc > 1.0) sc = 1.0;
+    p = (sc - eta) / (1.0 - eta);
+    if (p < 0.0) p = 0.0;
+  }
+  uint64_t z = seed + (frame_index + 1) * 0x9E3779B97F4A7C15ULL;
+  double u = (double)(splitmix64_mix(z) >> 11) * (1.0 / 9007199254740992.0);
+  if (prob) *prob = p;
+  return u < p ? 1 : 0;
+}
+
+int sdstream_ssf(sdstream_t* h, const uint8_t* frame, int32_t height, int32_t width, double eta, uint64_t seed,
+                 uint64_t frame_index, int32_t* skip, double* prob, void* hip_stream) {
+  if (!h) return SDSTREAM_E_INVALID_ARG;
+  if (!frame || !skip) return fail(h, SDSTREAM_E_INVALID_ARG, "null argument");
+  if (height < 1 || width < 1) return fail(h, SDSTREAM_E_SHAPE, "frame %dx%d", height, width);
+  if (((uintptr_t)frame) & 15) return fail(h, SDSTREAM_E_INVALID_ARG, "frame must be 16-byte aligned");
+  const long long n = (long long)height * width * 3;
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (n != h->ssf_n) {
+    HIP_TRY(h, hipDeviceSynchronize());
+    for (int i = 0; i < 2; ++i) {
+      if (h->ssf_buf[i]) hipFree(h->ssf_buf[i]);
+      h->ssf_buf[i] = nullptr;
+      HIP_TRY(h, hipMalloc((void**)&h->ssf_buf[i], (size_t)n + 16));
+    }
+    if (!h->ssf_sums) HIP_TRY(h, hipMalloc((void**)&h->ssf_sums, 4 * sizeof(unsigned long long)));
+    if (!h->ssf_host) HIP_TRY(h, hipHostMalloc((void**)&h->ssf_host, 4 * sizeof(unsigned long long), hipHostMallocDefault));
+    h->ssf_n = n;
+    h->ssf_ref = -1;
+  }
+  const uint8_t* ref = h->ssf_ref >= 0 ? h->ssf_buf[h->ssf_ref] : nullptr;
+  const int spare = h->ssf_ref >= 0 ? h->ssf_ref ^ 1 : 0;
+  launch_ssf_reduce(frame, ref, h->ssf_buf[spare], n, h->ssf_sums, s);
+  HIP_TRY(h, hipMemcpyAsync(h->ssf_host, h->ssf_sums, 2 * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
+  HIP_TRY(h, hipStreamSynchronize(s));
+  const uint64_t dot = h->ssf_host[0], nt = h->ssf_host[1];
+  double p = 0.0;
+  int sk = sdstream_ssf_decide(dot, nt, ref ? h->ssf_ref_norm : 0, eta, seed, frame_index, &p);
+  if (!ref) { sk = 0; p = 0.0; }
+  if (!sk) {
+    h->ssf_ref = spare;
+    h->ssf_ref_norm = nt;
+  }
+  *skip = sk;
+  if (prob) *prob = p;
+  return SDSTREAM_OK;
+}
+
+int sdstream_profile_enable(sdstream_t* h, int32_t on) {
+  if (!h) return SDSTREAM_E_INVALID_ARG;
+  h->profiling = on != 0;
+  return SDSTREAM_OK;
+}
+
+static int prof_drain(sdstream* h) {
+  HIP_TRY(h, hipDeviceSynchronize());
+  for (auto& r : h->prof_pending) {
+    float ms = 0.f;
+    hipEventElapsedTime(&ms, r.a, r.b);
+    sdstream_profile_entry& e = h->prof[r.cls];
+    e.launches += 1;
+    e.ms += ms;
+    e.flops += r.flops;
+    e.bytes += r.bytes;
+    hipEventDestroy(r.a);
+    hipEventDestroy(r.b);
+  }
+  h->prof_pending.clear();
+  return SDSTREAM_OK;
+}
+
+int sdstream_profile_reset(sdstream_t* h) {
+  if (!h) return SDSTREAM_E_INVALID_ARG;
+  int rc = prof_drain(h);
+  if (rc) return rc;
+  memset(h->prof, 0, sizeof h->prof);
+  return SDSTREAM_OK;
+}
+
+int32_t sdstream_profile_read(sdstream_t* h, sdstream_profile_entry* out, int32_t cap) {
+  if (!h || !out) return SDSTREAM_E_INVALID_ARG;
+  int rc = prof_drain(h);
+  if (rc) return rc;
+  int n = 0;
+  for (int c = 0; c < PC_COUNT && n < cap; ++c) {
+    if (!h->prof[c].launches) continue;
+    out[n] = h->prof[c];
+    strncpy(out[n].name, kProfNames[c], sizeof out[n].name - 1);
+    out[n].name[sizeof out[n].name - 1] = 0;
+    ++n;
+  }
+  return n;
+}
+
+int sdstream_use_graph(sdstream_t* h, int32_t on) {
+  if (!h) return SDSTREAM_E_INVALID_ARG;
+  h->graph_enabled = on != 0;
+  return SDSTREAM_OK;
+}
+
+}  // extern "C"

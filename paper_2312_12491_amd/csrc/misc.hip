@@ -1,0 +1,317 @@
+// Small kernels: first/last convolution (NCHW fp32 boundary <-> NHWC activations), time embedding,
+// the Stream Batch head (noise-in, batch assembly) and tail (guidance, scheduler update, queue shift),
+// the similarity-filter reduction and weight repacking.
+#include "common.h"
+
+namespace {
+
+// ---------------------------------------------------------------- conv_in
+template <typename T>
+__global__ __launch_bounds__(256) void conv_in_kernel(const float* __restrict__ x, const float* __restrict__ w,
+                                                      const float* __restrict__ b, T* __restrict__ out, int N, int Cin,
+                                                      int H, int W, int C0) {
+  long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  long long total = (long long)N * H * W * C0;
+  if (i >= total) return;
+  int co = (int)(i % C0);
+  long long pix = i / C0;
+  int xx = (int)(pix % W);
+  int yy = (int)((pix / W) % H);
+  int n = (int)(pix / ((long long)W * H));
+  float acc = b[co];
+  for (int ci = 0; ci < Cin; ++ci)
+    for (int ky = 0; ky < 3; ++ky) {
+      int iy = yy + ky - 1;
+      if (iy < 0 || iy >= H) continue;
+      for (int kx = 0; kx < 3; ++kx) {
+        int ix = xx + kx - 1;
+        if (ix < 0 || ix >= W) continue;
+        acc = fmaf(w[((co * Cin + ci) * 3 + ky) * 3 + kx], x[(((long long)n * Cin + ci) * H + iy) * W + ix], acc);
+      }
+    }
+  out[i] = from_f32<T>(acc);
+}
+
+// ---------------------------------------------------------------- conv_out: one wave per output pixel
+template <typename T>
+__global__ __launch_bounds__(256) void conv_out_kernel(const T* __restrict__ x, const T* __restrict__ w,
+                                                       const float* __restrict__ b, float* __restrict__ out, int N,
+                                                       int Cout, int H, int W, int C0) {
+  const int lane = threadIdx.x & 63;
+  long long pix = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (pix >= (long long)N * H * W) return;
+  int xx = (int)(pix % W);
+  int yy = (int)((pix / W) % H);
+  int n = (int)(pix / ((long long)W * H));
+  for (int co = 0; co < Cout; ++co) {
+    float acc = 0.f;
+    for (int tap = 0; tap < 9; ++tap) {
+      int iy = yy + tap / 3 - 1, ix = xx + tap % 3 - 1;
+      if (iy < 0 || iy >= H || ix < 0 || ix >= W) continue;
+      const T* src = x + (((long long)n * H + iy) * W + ix) * C0;
+      const T* wr = w + ((long long)co * 9 + tap) * C0;
+      for (int c = lane; c < C0; c += 64) acc = fmaf(to_f32<T>(src[c]), to_f32<T>(wr[c]), acc);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+    if (lane == 0) out[(((long long)n * Cout + co) * H + yy) * W + xx] = acc + b[co];
+  }
+}
+
+// ---------------------------------------------------------------- time embedding
+__global__ void time_embedding_kernel(const int* t, float* out, int rows, int C0) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  int half = C0 / 2;
+  if (i >= rows * half) return;
+  int r = i / half, j = i - r * half;
+  double f = exp(-log(10000.0) * (double)j / (double)half);
+  double a = (double)t[r] * f;
+  out[(long long)r * C0 + j] = (float)cos(a);
+  out[(long long)r * C0 + half + j] = (float)sin(a);
+}
+
+// ---------------------------------------------------------------- Stream Batch head / tail
+// rows of the U-Net batch: row = s*n + i (stream s, slot i); extra rows after S*n:
+//   full CFG: a second copy of every row (negative prompt); onetime: one copy of slot 0 per stream.
+__global__ __launch_bounds__(256) void stream_head_kernel(StreamParams p) {
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  long long per = (long long)p.S * p.E;
+  if (idx >= per) return;
+  int s = (int)(idx / p.E);
+  int e = (int)(idx - (long long)s * p.E);
+  float x0 = p.x0_in[idx];
+  float x = p.a[0] * x0 + p.b[0] * p.noise[idx];  // Eq. 1; noise[0][s][e]
+  long long row0 = (long long)s * p.n;
+  p.xcur[row0 * p.E + e] = x;
+  if (p.mode == 2) p.rcur[row0 * p.E + e] = x0;
+  if (p.mode == 3) p.xcur[((long long)p.S * p.n + s) * p.E + e] = x;
+  if (p.mode == 1) {
+    for (int i = 0; i < p.n; ++i) {
+      long long r = row0 + i;
+      p.xcur[((long long)p.S * p.n + r) * p.E + e] = i == 0 ? x : p.xcur[r * p.E + e];
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void stream_tail_kernel(StreamParams p) {
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  long long total = (long long)p.S * p.n * p.E;
+  if (idx >= total) return;
+  long long row = idx / p.E;
+  int e = (int)(idx - row * p.E);
+  int s = (int)(row / p.n), i = (int)(row - (long long)s * p.n);
+  const float a = p.a[i], b = p.b[i];
+  const float x = p.xcur[idx];
+  const float E = p.eps[idx];
+  float G, ref = 0.f;
+  if (p.mode == 0) {
+    G = E;
+  } else if (p.mode == 1) {
+    float Nn = p.eps[((long long)p.S * p.n + row) * p.E + e];
+    G = Nn + p.gamma * (E - Nn);  // Eq. 2
+  } else {
+    if (p.mode == 3 && i == 0) {
+      float En = p.eps[((long long)p.S * p.n + s) * p.E + e];
+      ref = (x - b * En) / a;  // Eq. 7
+    } else {
+      ref = p.rcur[idx];
+    }
+    float V = (x - a * ref) / b;                      // Eq. 5
+    G = p.delta * V + p.gamma * (E - p.delta * V);    // Eq. 6
+  }
+  const float X0 = (x - b * G) / a;  // Eq. 4 with c_skip = 0, c_out = 1
+  if (i < p.n - 1) {
+    float nxt = p.scheduler == 0 ? p.noise[((long long)(i + 1) * p.S + s) * p.E + e] : G;
+    p.xnext[idx + p.E] = p.a[i + 1] * X0 + p.b[i + 1] * nxt;
+    if (p.mode >= 2) p.rnext[idx + p.E] = ref;
+  } else {
+    p.out[(long long)s * p.E + e] = X0;
+  }
+}
+
+// ---------------------------------------------------------------- SSF reduction (exact integers)
+__global__ __launch_bounds__(256) void ssf_reduce_kernel(const uint8_t* __restrict__ f, const uint8_t* __restrict__ r,
+                                                         uint8_t* __restrict__ spare, long long n,
+                                                         unsigned long long* sums) {
+  unsigned long long dot = 0, nt = 0;
+  const long long nvec = n / 16;
+  const uint4* f4 = (const uint4*)f;
+  const uint4* r4 = (const uint4*)r;
+  uint4* s4 = (uint4*)spare;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < nvec;
+       i += (long long)gridDim.x * blockDim.x) {
+    uint4 a = f4[i];
+    uint4 b = r ? r4[i] : make_uint4(0, 0, 0, 0);
+    s4[i] = a;
+    unsigned d = 0, q = 0;  // 16 products of at most 255*255 fit in 32 bits
+    d = __builtin_amdgcn_udot4(a.x, b.x, d, false);
+    d = __builtin_amdgcn_udot4(a.y, b.y, d, false);
+    d = __builtin_amdgcn_udot4(a.z, b.z, d, false);
+    d = __builtin_amdgcn_udot4(a.w, b.w, d, false);
+    q = __builtin_amdgcn_udot4(a.x, a.x, q, false);
+    q = __builtin_amdgcn_udot4(a.y, a.y, q, false);
+    q = __builtin_amdgcn_udot4(a.z, a.z, q, false);
+    q = __builtin_amdgcn_udot4(a.w, a.w, q, false);
+    dot += d;
+    nt += q;
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) {  // ragged tail, byte by byte
+    for (long long i = nvec * 16; i < n; ++i) {
+      unsigned a = f[i], b = r ? r[i] : 0;
+      spare[i] = (uint8_t)a;
+      dot += a * b;
+      nt += a * a;
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    dot += __shfl_xor(dot, o);
+    nt += __shfl_xor(nt, o);
+  }
+  __shared__ unsigned long long red[2][4];
+  if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = dot; red[1][threadIdx.x >> 6] = nt; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    atomicAdd(&sums[0], red[0][0] + red[0][1] + red[0][2] + red[0][3]);
+    atomicAdd(&sums[1], red[1][0] + red[1][1] + red[1][2] + red[1][3]);
+  }
+}
+
+// ---------------------------------------------------------------- weight repacking
+__device__ __forceinline__ int geglu_src_row(int r, int O, int blk) {
+  if (blk <= 0) return r;
+  int q = r / (2 * blk), w = r - q * 2 * blk;
+  return w < blk ? q * blk + w : O / 2 + q * blk + (w - blk);
+}
+
+// dst[o][tap][i] = src[orow][i][tap]   (orow = GEGLU-interleaved source row)
+template <typename T>
+__global__ void repack_rowmajor_kernel(const float* src, T* dst, int O, int I, int taps, int blk) {
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  long long total = (long long)O * I * taps;
+  if (idx >= total) return;
+  int i = (int)(idx % I);
+  int tap = (int)((idx / I) % taps);
+  int o = (int)(idx / ((long long)I * taps));
+  int so = geglu_src_row(o, O, blk);
+  dst[idx] = from_f32<T>(src[((long long)so * I + i) * taps + tap]);
+}
+
+// MFMA B-fragment order for v_mfma_f32_16x16x32_bf16: dst[ntile][kstep][lane][8] with
+// column n = ntile*16 + lane%16 and k = kstep*32 + (lane/16)*8 + j, k = tap*I + i.
+__global__ void repack_mfma_kernel(const float* src, bf16_t* dst, int O, int I, int taps, int blk) {
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  long long K = (long long)I * taps;
+  long long total = (long long)O * K;
+  if (idx >= total) return;
+  int j = (int)(idx & 7);
+  int lane = (int)((idx >> 3) & 63);
+  long long frag = idx >> 9;
+  long long ksteps = K / 32;
+  int kstep = (int)(frag % ksteps);
+  int ntile = (int)(frag / ksteps);
+  int n = ntile * 16 + (lane & 15);
+  long long k = (long long)kstep * 32 + (lane >> 4) * 8 + j;
+  int tap = (int)(k / I), i = (int)(k - (long long)tap * I);
+  int so = geglu_src_row(n, O, blk);
+  dst[idx] = (bf16_t)src[((long long)so * I + i) * taps + tap];
+}
+
+__global__ void permute_bias_kernel(const float* src, float* dst, int O, int blk) {
+  int o = blockIdx.x * blockDim.x + threadIdx.x;
+  if (o < O) dst[o] = src[geglu_src_row(o, O, blk)];
+}
+
+template <typename T> __global__ void convert_kernel(const float* src, T* dst, long long n) {
+  long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = from_f32<T>(src[i]);
+}
+
+__global__ void fill_u32_kernel(unsigned* dst, unsigned v, long long n) {
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x)
+    dst[i] = v;
+}
+
+__global__ void copy_f32_kernel(const float* src, float* dst, long long n) {
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
+inline unsigned blocks_for(long long n, int per = 256, long long cap = 1 << 20) {
+  long long b = (n + per - 1) / per;
+  if (b < 1) b = 1;
+  if (b > cap) b = cap;
+  return (unsigned)b;
+}
+
+}  // namespace
+
+template <typename T>
+void launch_conv_in(const float* x, const float* w, const float* b, void* out, int N, int Cin, int H, int W, int C0,
+                    hipStream_t s) {
+  long long total = (long long)N * H * W * C0;
+  hipLaunchKernelGGL(conv_in_kernel<T>, dim3(blocks_for(total, 256, 1LL << 31)), dim3(256), 0, s, x, w, b, (T*)out, N,
+                     Cin, H, W, C0);
+}
+template void launch_conv_in<float>(const float*, const float*, const float*, void*, int, int, int, int, int, hipStream_t);
+template void launch_conv_in<bf16_t>(const float*, const float*, const float*, void*, int, int, int, int, int, hipStream_t);
+
+template <typename T>
+void launch_conv_out(const void* x, const void* w, const float* b, float* out, int N, int Cout, int H, int W, int C0,
+                     hipStream_t s) {
+  long long pix = (long long)N * H * W;
+  hipLaunchKernelGGL(conv_out_kernel<T>, dim3((unsigned)((pix + 3) / 4)), dim3(256), 0, s, (const T*)x, (const T*)w, b,
+                     out, N, Cout, H, W, C0);
+}
+template void launch_conv_out<float>(const void*, const void*, const float*, float*, int, int, int, int, int, hipStream_t);
+template void launch_conv_out<bf16_t>(const void*, const void*, const float*, float*, int, int, int, int, int, hipStream_t);
+
+void launch_time_embedding(const int* t, float* out, int rows, int C0, hipStream_t s) {
+  int total = rows * (C0 / 2);
+  hipLaunchKernelGGL(time_embedding_kernel, dim3((total + 127) / 128), dim3(128), 0, s, t, out, rows, C0);
+}
+
+void launch_stream_head(const StreamParams& p, hipStream_t s) {
+  hipLaunchKernelGGL(stream_head_kernel, dim3(blocks_for((long long)p.S * p.E)), dim3(256), 0, s, p);
+}
+void launch_stream_tail(const StreamParams& p, hipStream_t s) {
+  hipLaunchKernelGGL(stream_tail_kernel, dim3(blocks_for((long long)p.S * p.n * p.E)), dim3(256), 0, s, p);
+}
+
+void launch_ssf_reduce(const uint8_t* frame, const uint8_t* ref, uint8_t* spare, long long n, unsigned long long* sums,
+                       hipStream_t s) {
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, s, (unsigned*)sums, 0u, 4LL);
+  hipLaunchKernelGGL(ssf_reduce_kernel, dim3(blocks_for(n / 16, 256, 512)), dim3(256), 0, s, frame, ref, spare, n, sums);
+}
+
+template <typename T>
+void launch_repack_rowmajor(const float* src, void* dst, int O, int I, int taps, int geglu_block, hipStream_t s) {
+  long long total = (long long)O * I * taps;
+  hipLaunchKernelGGL(repack_rowmajor_kernel<T>, dim3(blocks_for(total, 256, 1LL << 31)), dim3(256), 0, s, src, (T*)dst,
+                     O, I, taps, geglu_block);
+}
+template void launch_repack_rowmajor<float>(const float*, void*, int, int, int, int, hipStream_t);
+template void launch_repack_rowmajor<bf16_t>(const float*, void*, int, int, int, int, hipStream_t);
+
+void launch_repack_mfma(const float* src, void* dst, int O, int I, int taps, int geglu_block, hipStream_t s) {
+  long long total = (long long)O * I * taps;
+  hipLaunchKernelGGL(repack_mfma_kernel, dim3(blocks_for(total, 256, 1LL << 31)), dim3(256), 0, s, src, (bf16_t*)dst, O,
+                     I, taps, geglu_block);
+}
+
+void launch_permute_bias(const float* src, float* dst, int O, int geglu_block, hipStream_t s) {
+  hipLaunchKernelGGL(permute_bias_kernel, dim3((O + 255) / 256), dim3(256), 0, s, src, dst, O, geglu_block);
+}
+
+template <typename T> void launch_convert(const float* src, void* dst, long long n, hipStream_t s) {
+  hipLaunchKernelGGL(convert_kernel<T>, dim3(blocks_for(n, 256, 1LL << 31)), dim3(256), 0, s, src, (T*)dst, n);
+}
+template void launch_convert<float>(const float*, void*, long long, hipStream_t);
+template void launch_convert<bf16_t>(const float*, void*, long long, hipStream_t);
+
+void launch_fill_u32(void* dst, unsigned v, long long n_words, hipStream_t s) {
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks_for(n_words, 256, 4096)), dim3(256), 0, s, (unsigned*)dst, v, n_words);
+}
+void launch_copy_rows_f32(const float* src, float* dst, long long n, hipStream_t s) {
+  hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks_for(n, 256, 4096)), dim3(256), 0, s, src, dst, n);
+}

@@ -1,0 +1,38 @@
+"""Helpers shared by the GPU parity tests: build an engine / an oracle net for one workload dict."""
+import numpy as np
+import torch
+
+from workloads import make_weights
+
+
+def rel_max(g, o):
+    g, o = np.asarray(g, dtype=np.float64), np.asarray(o, dtype=np.float64)
+    return float(np.abs(g - o).max() / np.abs(o).max())
+
+
+def rel_l2(g, o):
+    g, o = np.asarray(g, dtype=np.float64), np.asarray(o, dtype=np.float64)
+    return float(np.linalg.norm(g - o) / np.linalg.norm(o))
+
+
+def oracle_net(wl, bf16_weights):
+    from oracle import unet as U
+    shape = U.UNetShape.from_dict(wl["unet"])
+    blob = make_weights(U.manifest(shape), wl["seeds"]["weights"], wl["init"], bf16_weights)
+    return U.UNet(shape, blob)
+
+
+def gpu_engine(wl, dtype, cfg_mode=0, scheduler=0, n_streams=None, timesteps=None, blob=None):
+    import paper_2312_12491_amd as sd
+    ts = wl["timesteps"] if timesteps is None else timesteps
+    S = wl["n_streams"] if n_streams is None else n_streams
+    cfg = sd.config_from_dict(wl["unet"], wl["latent"], dtype, len(ts), S, cfg_mode, scheduler)
+    eng = sd.Engine(cfg)
+    if blob is None:
+        blob = make_weights(eng.manifest(), wl["seeds"]["weights"], wl["init"], dtype == "bf16")
+    eng.load_weights(blob)
+    return eng
+
+
+def cuda(a):
+    return torch.as_tensor(np.ascontiguousarray(a)).cuda()
