@@ -252,7 +252,7 @@ struct Builder {
     if (!e.use_mfma || !igemm_mfma_available()) return false;
     if (C1 % 32 || C2 % 32) return false;
     if (N % 16) return false;
-    if (geglu && N % 32) return false;
+    if (geglu && N % 128) return false;
     return true;
   }
   // a conv / linear weight in the activation dtype; `ksz` 1 or 3; canonical shape OIHW or [O,I]
