@@ -71,6 +71,9 @@ struct PlanAllocator {
   }
 };
 
+// split-K is used only for GEMMs with few output tiles; splits * M * N never exceeds this
+constexpr size_t kSplitKWorkspaceFloats = (size_t)16 << 20;
+
 enum OpKind { OP_IGEMM, OP_GN, OP_LN, OP_ATTN, OP_CONV_IN, OP_CONV_OUT };
 enum ProfClass {
   PC_IGEMM_MFMA, PC_IGEMM_VALU, PC_ATTN_MFMA, PC_ATTN_VALU, PC_GROUP_NORM, PC_LAYER_NORM, PC_CONV_IN, PC_CONV_OUT,
@@ -155,6 +158,8 @@ struct sdstream {
   size_t off_sel_zero = 0, off_sel_step = 0;
   size_t off_x[2] = {0, 0}, off_r[2] = {0, 0}, off_eps = 0, off_noise = 0, off_ab = 0;
   size_t off_unet_x = 0;  // fp32 input batch for unet_forward
+  size_t off_zeros = 0;   // 256 bytes that stay zero
+  size_t off_splitk = 0;  // fp32 [M][N] accumulator of split-K GEMMs, zero between launches
   double flops_per_row = 0;
 
   // state
@@ -183,7 +188,7 @@ struct sdstream {
 
   // profiling
   bool profiling = false;
-  struct ProfRec { int cls; hipEvent_t a, b; double flops, bytes; };
+  struct ProfRec { int cls; hipEvent_t a, b; double flops, bytes; int op; int N; };
   std::vector<ProfRec> prof_pending;
   sdstream_profile_entry prof[PC_COUNT];
 };
@@ -536,6 +541,8 @@ struct Builder {
     e.off_noise = palloc(rows_state * e.E * 4);
     e.off_ab = palloc((size_t)2 * c.n_denoise * 4);
     e.off_unet_x = palloc((size_t)e.max_batch * e.E * 4);
+    e.off_splitk = palloc(kSplitKWorkspaceFloats * 4);
+    e.off_zeros = palloc(256);
 
     // time embedding MLP (float32)
     LinW t1 = f32w("time.lin1", temb_dim, c0);
@@ -735,7 +742,24 @@ void launch_op(sdstream* h, const Op& op0, int N, const int* kv_select, hipStrea
     case OP_IGEMM: {
       IgemmParams g = op0.g;
       g.M = N * op0.rows_per_sample;
-      if (op0.mfma) launch_igemm_mfma(g, s);
+      g.zeros = h->persist + h->off_zeros;
+      if (op0.mfma) {
+        // few output tiles: split K across blocks so the whole chip streams the weights
+        const int bn = g.N % 160 == 0 ? 160 : (g.N % 128 == 0 ? 128 : 64);
+        const int tiles = ((g.M + 127) / 128) * ((g.N + bn - 1) / bn);
+        const int stages = g.K / 64;
+        if (g.epilogue == EPI_NONE && tiles <= 128 && stages >= 8) {
+          int sk = 512 / tiles;
+          if (sk > stages / 4) sk = stages / 4;
+          const size_t mn = (size_t)g.M * g.N;
+          if ((size_t)sk * mn > kSplitKWorkspaceFloats) sk = (int)(kSplitKWorkspaceFloats / mn);
+          if (sk > 1) {
+            g.splitk = sk;
+            g.workspace = (float*)(h->persist + h->off_splitk);
+          }
+        }
+        launch_igemm_mfma(g, s);
+      }
       else if (bf) launch_igemm_generic<bf16_t>(g, s);
       else launch_igemm_generic<float>(g, s);
       break;
@@ -778,9 +802,9 @@ void launch_op(sdstream* h, const Op& op0, int N, const int* kv_select, hipStrea
   }
 }
 
-int prof_begin(sdstream* h, int cls, double flops, double bytes, hipStream_t s) {
+int prof_begin(sdstream* h, int cls, double flops, double bytes, hipStream_t s, int op = -1, int N = 0) {
   sdstream::ProfRec r;
-  r.cls = cls; r.flops = flops; r.bytes = bytes;
+  r.cls = cls; r.flops = flops; r.bytes = bytes; r.op = op; r.N = N;
   HIP_TRY(h, hipEventCreate(&r.a));
   HIP_TRY(h, hipEventCreate(&r.b));
   HIP_TRY(h, hipEventRecord(r.a, s));
@@ -815,9 +839,10 @@ int run_unet(sdstream* h, const float* x, float* eps, int N, const int* kv_selec
     }
     HIP_TRY(h, hipGraphLaunch(it->second, s));
   } else {
-    for (const Op& op : h->ops) {
+    for (size_t oi = 0; oi < h->ops.size(); ++oi) {
+      const Op& op = h->ops[oi];
       if (h->profiling) {
-        int rc = prof_begin(h, op.cls, op.flops_per_row * N, op.bytes_per_row * N + op.bytes_fixed, s);
+        int rc = prof_begin(h, op.cls, op.flops_per_row * N, op.bytes_per_row * N + op.bytes_fixed, s, (int)oi, N);
         if (rc) return rc;
       }
       launch_op(h, op, N, kv_select, s);
@@ -870,6 +895,7 @@ int build_kv(sdstream* h, const float* ctx, const float* neg, hipStream_t s) {
       g.W = h->weights + site.w.w;
       g.out = h->persist + site.cache + (size_t)slot * c.context_len * 2 * site.C * h->elt;
       g.splitk = 1;
+      g.zeros = h->persist + h->off_zeros;
       if (site.w.mfma) launch_igemm_mfma(g, s);
       else if (bf) launch_igemm_generic<bf16_t>(g, s);
       else launch_igemm_generic<float>(g, s);
@@ -1208,6 +1234,19 @@ static int prof_drain(sdstream* h) {
   for (auto& r : h->prof_pending) {
     float ms = 0.f;
     hipEventElapsedTime(&ms, r.a, r.b);
+    if (r.op >= 0 && getenv("SDSTREAM_PROFILE_OPS")) {
+      const Op& op = h->ops[r.op];
+      if (op.kind == OP_IGEMM)
+        fprintf(stderr, "op %3d %-11s M=%d N=%d K=%d ks=%d st=%d up=%d epi=%d res=%d  %.1f us  %.1f TF/s\n", r.op,
+                kProfNames[r.cls], r.N * op.rows_per_sample, op.g.N, op.g.K, op.g.ksize, op.g.stride, op.g.upsample,
+                op.g.epilogue, op.g.residual ? 1 : 0, ms * 1e3, r.flops / (ms * 1e-3) / 1e12);
+      else if (op.kind == OP_ATTN)
+        fprintf(stderr, "op %3d %-11s Sq=%d Skv=%d heads=%d d=%d  %.1f us  %.1f TF/s\n", r.op, kProfNames[r.cls],
+                op.at.Sq, op.at.Skv, op.at.heads, op.at.d, ms * 1e3, r.flops / (ms * 1e-3) / 1e12);
+      else
+        fprintf(stderr, "op %3d %-11s rows=%d  %.1f us  %.1f GB/s\n", r.op, kProfNames[r.cls],
+                r.N * op.rows_per_sample, ms * 1e3, r.bytes / (ms * 1e-3) / 1e9);
+    }
     sdstream_profile_entry& e = h->prof[r.cls];
     e.launches += 1;
     e.ms += ms;

@@ -4,13 +4,13 @@
 //
 // Work split: one 256-thread block (4 waves, 2x2) owns a BM x BN output tile.  The activation tile
 // (implicit im2col rows, gathered from NHWC with zero padding, stride, nearest-2x upsample and a second
-// concatenated source folded into the indexing) is staged through double-buffered LDS; the weights are
+// concatenated source folded into the indexing) is staged through double-buffered LDS in 32-deep K stages; the weights are
 // stored pre-packed in MFMA fragment order and go from global memory straight into registers, one coalesced
-// 1 KB read per fragment, prefetched one stage ahead.  The MFMA is issued with the weight fragment as the
+// 1 KB read per fragment.  Both are prefetched into a ring of register sets several stages ahead.  The MFMA is issued with the weight fragment as the
 // row operand, so every lane ends up with 4 consecutive output channels of one pixel: bias, time-embedding
 // bias, GEGLU and the residual are applied on registers and stored as 8-byte vectors.
-// Optional split-K (grid.z) accumulates fp32 partials with atomics into a zeroed workspace that a small
-// finalize kernel turns into the output (and zeroes again).
+// Optional split-K (grid.z) writes fp32 partial tiles to a workspace that a small finalize kernel sums and
+// turns into the output.
 #include "common.h"
 
 namespace {
@@ -18,18 +18,21 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
 
-template <int BM, int BN, int KS>
-__global__ __launch_bounds__(256) void igemm_mfma_kernel(IgemmParams p, int mtiles, int ksteps_total,
+template <int I> struct IC { static constexpr int value = I; };
+
+template <int BM, int BN, int NSETS>
+__global__ __launch_bounds__(256, 2) void igemm_mfma_kernel(IgemmParams p, int mtiles, int ksteps_total,
                                                          int stages_per_split) {
   constexpr int WM = 2, WN = 2;
-  constexpr int KC = 32 * KS;
   constexpr int WTM = BM / WM, WTN = BN / WN, MT = WTM / 16, NT = WTN / 16;
-  constexpr int ROWB = KC * 2 + 16;   // LDS row pitch in bytes (pad keeps 16-lane b128 reads conflict-free)
-  constexpr int CPR = KC / 8;         // 16-byte chunks per row
-  constexpr int NLD = BM * CPR / 256; // chunks each thread stages
+  constexpr int ROWB = 80;             // LDS row pitch: 32 bf16 + 16 bytes pad (16-lane b128 reads hit 64 distinct banks)
+  constexpr int CPR = 4;               // 16-byte chunks per row
+  constexpr int NLD = BM * CPR / 256;  // chunks each thread stages
+  constexpr int D = NSETS - 1;         // prefetch distance in 32-deep K stages
   __shared__ __attribute__((aligned(16))) unsigned char lds[2][BM * ROWB];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -40,19 +43,20 @@ __global__ __launch_bounds__(256) void igemm_mfma_kernel(IgemmParams p, int mtil
   const int pad = p.ksize >> 1;
   const int HWo = p.Hout * p.Wout;
   const int Hs = p.upsample ? p.Hin * 2 : p.Hin, Wsz = p.upsample ? p.Win * 2 : p.Win;
-  const bf16_t* s1 = (const bf16_t*)p.src1;
-  const bf16_t* s2 = (const bf16_t*)p.src2;
-  const bf16_t* Wp = (const bf16_t*)p.W;
+  const int ups = p.upsample;
+  const char* s1 = (const char*)p.src1;
+  const char* s2 = (const char*)p.src2;
+  const char* Wp = (const char*)p.W;
 
-  // ---- loader slots of this thread
-  int ld_y[NLD], ld_x[NLD], ld_row[NLD];
-  long long ld_base[NLD];
+  // ---- loader slots of this thread: output pixel of the row, top-left tap position, LDS address
+  int ld_y[NLD], ld_x[NLD], ld_lds[NLD];
+  unsigned ld_pix0[NLD];
   bool ld_ok[NLD];
-  const int cq = tid % CPR;
+  const int cq = tid & (CPR - 1);
 #pragma unroll
   for (int i = 0; i < NLD; ++i) {
     int row = (tid + i * 256) / CPR;
-    ld_row[i] = row;
+    ld_lds[i] = row * ROWB + cq * 16;
     int m = m0 + row;
     ld_ok[i] = m < p.M;
     int mm = ld_ok[i] ? m : 0;
@@ -61,57 +65,66 @@ __global__ __launch_bounds__(256) void igemm_mfma_kernel(IgemmParams p, int mtil
     int oy = r / p.Wout, ox = r - oy * p.Wout;
     ld_y[i] = oy * p.stride - pad;
     ld_x[i] = ox * p.stride - pad;
-    ld_base[i] = (long long)n * p.Hin * p.Win;
+    ld_pix0[i] = (unsigned)n * (unsigned)(p.Hin * p.Win);
   }
 
-  // ---- K range of this split
+  // ---- K range of this split, and the cursor of the next stage to load
   const int stage0 = blockIdx.z * stages_per_split;
-  const int total_stages = ksteps_total / KS;
-  int nstages = total_stages - stage0;
+  int nstages = ksteps_total - stage0;
   if (nstages > stages_per_split) nstages = stages_per_split;
-  int kk = stage0 * KC;
-  int tap = kk / Ct, cch = kk - tap * Ct;
-  int ky = tap / p.ksize, kx = tap - ky * p.ksize;
+  int l_k32 = stage0;
+  const int k32_last = ksteps_total - 1;
+  int l_c, l_ky, l_kx;
+  {
+    int kk = stage0 * 32;
+    int tap = kk / Ct;
+    l_c = kk - tap * Ct;
+    l_ky = tap / p.ksize;
+    l_kx = tap - l_ky * p.ksize;
+  }
 
-  // weight fragments of this wave: global n-tile index gnt0 + nt
+  // weight fragments of this wave: global n-tile index gnt0 + nt, 1 KB per (n-tile, k-step)
   const int gnt0 = (n0 + wn * WTN) >> 4;
   const int ntiles_total = p.N >> 4;
+  unsigned boff[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    int g = gnt0 + nt;
+    if (g >= ntiles_total) g = ntiles_total - 1;  // columns past N are computed on valid data and dropped
+    boff[nt] = ((unsigned)g * (unsigned)ksteps_total * 64u + (unsigned)lane) * 16u;
+  }
 
-  uint4 areg[NLD];
-  bf16x8 bcur[KS][NT], bnxt[KS][NT];
+  u32x4 areg[NSETS][NLD];
+  bf16x8 breg[NSETS][NT];
+  unsigned okm[NSETS];
 
-  auto load_a = [&]() {
-    const bf16_t* src;
-    int Cs, c = cch;
+  // issues the global loads of the cursor's stage into register set `set` (no waits, no branches):
+  // rows in the padding read a clamped in-range pixel and are zeroed when they are written to LDS
+  auto load = [&](auto setc) {
+    constexpr int set = decltype(setc)::value;
+    const char* src;
+    int Cs, c = l_c;
     if (c < p.C1) { src = s1; Cs = p.C1; } else { src = s2; Cs = p.C2; c -= p.C1; }
+    unsigned m = 0;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      int iy = ld_y[i] + ky, ix = ld_x[i] + kx;
-      bool ok = ld_ok[i] && iy >= 0 && iy < Hs && ix >= 0 && ix < Wsz;
-      if (p.upsample) { iy >>= 1; ix >>= 1; }
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (ok) v = *(const uint4*)(src + (ld_base[i] + (long long)iy * p.Win + ix) * Cs + c + cq * 8);
-      areg[i] = v;
+      int iy = ld_y[i] + l_ky, ix = ld_x[i] + l_kx;
+      bool ok = ld_ok[i] && (unsigned)iy < (unsigned)Hs && (unsigned)ix < (unsigned)Wsz;
+      iy = min(max(iy, 0), Hs - 1) >> ups;
+      ix = min(max(ix, 0), Wsz - 1) >> ups;
+      unsigned off = ((ld_pix0[i] + (unsigned)(iy * p.Win + ix)) * (unsigned)Cs + (unsigned)(c + cq * 8)) * 2u;
+      areg[set][i] = *(const u32x4*)(src + off);
+      m |= (ok ? 1u : 0u) << i;
     }
-  };
-  auto load_b = [&](bf16x8 (&b)[KS][NT], int kstep) {
+    okm[set] = m;
+    const unsigned kb = (unsigned)min(l_k32, k32_last) * 1024u;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        int g = gnt0 + nt;
-        if (g < ntiles_total)
-          b[ks][nt] = *(const bf16x8*)(Wp + (((long long)g * ksteps_total + kstep + ks) * 64 + lane) * 8);
-        else
-          b[ks][nt] = bf16x8{};
-      }
-  };
-  auto advance = [&]() {
-    kk += KC;
-    cch += KC;
-    if (cch >= Ct) {
-      cch = 0;
-      if (++kx == p.ksize) { kx = 0; ++ky; }
+    for (int nt = 0; nt < NT; ++nt) breg[set][nt] = *(const bf16x8*)(Wp + (boff[nt] + kb));
+    ++l_k32;
+    l_c += 32;
+    if (l_c >= Ct) {
+      l_c = 0;
+      if (++l_kx == p.ksize) { l_kx = 0; ++l_ky; }
     }
   };
 
@@ -121,37 +134,45 @@ __global__ __launch_bounds__(256) void igemm_mfma_kernel(IgemmParams p, int mtil
 #pragma unroll
     for (int j = 0; j < NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  if (nstages > 0) {
-    load_a();
-    load_b(bcur, kk / 32);
-  }
   int buf = 0;
-  for (int s = 0; s < nstages; ++s) {
+  // one 32-deep stage: stage the activations loaded D stages ago, sync, prefetch D stages ahead, multiply
+  auto stage = [&](auto setc) {
+    constexpr int set = decltype(setc)::value;
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) *(uint4*)(&lds[buf][ld_row[i] * ROWB + cq * 16]) = areg[i];
-    __syncthreads();
-    if (s + 1 < nstages) {
-      advance();
-      load_a();
-      load_b(bnxt, kk / 32);
+    for (int i = 0; i < NLD; ++i) {
+      u32x4 v = areg[set][i];
+      if (!((okm[set] >> i) & 1u)) v = u32x4{0u, 0u, 0u, 0u};
+      *(u32x4*)(&lds[buf][ld_lds[i]]) = v;
     }
+    __syncthreads();
+    load(IC<(set + D) % NSETS>{});  // unconditional: past the end the cursor re-reads in-range data that is never used
+    bf16x8 af[MT];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      bf16x8 af[MT];
+    for (int mt = 0; mt < MT; ++mt)
+      af[mt] = *(const bf16x8*)(&lds[buf][(wm * WTM + mt * 16 + (lane & 15)) * ROWB + (lane >> 4) * 16]);
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
-        af[mt] = *(const bf16x8*)(&lds[buf][(wm * WTM + mt * 16 + (lane & 15)) * ROWB + (ks * 32 + (lane >> 4) * 8) * 2]);
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bcur[ks][nt], af[mt], acc[mt][nt], 0, 0, 0);
-    }
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) bcur[ks][nt] = bnxt[ks][nt];
+        acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(breg[set][nt], af[mt], acc[mt][nt], 0, 0, 0);
     buf ^= 1;
+  };
+
+  load(IC<0>{});
+  if constexpr (D > 1) load(IC<1>{});
+  if constexpr (D > 2) load(IC<2>{});
+  for (int base = 0; base < nstages; base += NSETS) {
+    stage(IC<0>{});
+    if (base + 1 >= nstages) break;
+    stage(IC<1>{});
+    if constexpr (NSETS > 2) {
+      if (base + 2 >= nstages) break;
+      stage(IC<2>{});
+    }
+    if constexpr (NSETS > 3) {
+      if (base + 3 >= nstages) break;
+      stage(IC<3>{});
+    }
   }
 
   // ---- epilogue: lane holds channels n..n+3 of pixel m
@@ -168,9 +189,7 @@ __global__ __launch_bounds__(256) void igemm_mfma_kernel(IgemmParams p, int mtil
       for (int nt = 0; nt < NT; ++nt) {
         const int n = (gnt0 + nt) * 16 + (lane >> 4) * 4;
         if (n >= p.N) continue;
-        float* w = p.workspace + (long long)m * p.N + n;
-#pragma unroll
-        for (int v = 0; v < 4; ++v) atomicAdd(w + v, acc[mt][nt][v]);
+        *(f32x4*)(p.workspace + ((long long)blockIdx.z * p.M + m) * p.N + n) = acc[mt][nt];
       }
       continue;
     }
@@ -212,15 +231,15 @@ __global__ __launch_bounds__(256) void igemm_mfma_kernel(IgemmParams p, int mtil
   }
 }
 
-// split-K finalize: workspace (fp32 [M][N]) -> out with the epilogue of the main kernel; re-zeroes the workspace
+// split-K finalize: sum of the partials (fp32 [splitk][M][N]) -> out with the epilogue of the main kernel
 __global__ __launch_bounds__(256) void igemm_finalize_kernel(IgemmParams p) {
   const long long idx4 = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   const long long total4 = (long long)p.M * p.N / 4;
   if (idx4 >= total4) return;
   const long long e = idx4 * 4;
   const int m = (int)(e / p.N), n = (int)(e - (long long)m * p.N);
-  f32x4 x = *(f32x4*)(p.workspace + e);
-  *(f32x4*)(p.workspace + e) = f32x4{0.f, 0.f, 0.f, 0.f};
+  f32x4 x = *(const f32x4*)(p.workspace + e);
+  for (int z = 1; z < p.splitk; ++z) x += *(const f32x4*)(p.workspace + (long long)z * p.M * p.N + e);
   if (p.bias) x += *(const f32x4*)(p.bias + n);
   if (p.rowbias) x += *(const f32x4*)(p.rowbias + (long long)(m / (p.Hout * p.Wout)) * p.rowbias_ld + n);
   if (p.residual) {
@@ -234,14 +253,14 @@ __global__ __launch_bounds__(256) void igemm_finalize_kernel(IgemmParams p) {
   *(bf16x4*)((bf16_t*)p.out + e) = o;
 }
 
-template <int BM, int BN, int KS> void launch_cfg(const IgemmParams& p, hipStream_t s) {
+template <int BM, int BN> void launch_cfg(const IgemmParams& p, hipStream_t s) {
+  constexpr int NSETS = 3;
   const int mtiles = (p.M + BM - 1) / BM, ntiles = (p.N + BN - 1) / BN;
   const int ksteps_total = p.K / 32;
-  const int total_stages = ksteps_total / KS;
   const int splitk = p.splitk > 1 ? p.splitk : 1;
-  const int sps = (total_stages + splitk - 1) / splitk;
+  const int sps = (ksteps_total + splitk - 1) / splitk;
   dim3 grid(mtiles * ntiles, 1, splitk);
-  hipLaunchKernelGGL((igemm_mfma_kernel<BM, BN, KS>), grid, dim3(256), 0, s, p, mtiles, ksteps_total, sps);
+  hipLaunchKernelGGL((igemm_mfma_kernel<BM, BN, NSETS>), grid, dim3(256), 0, s, p, mtiles, ksteps_total, sps);
   if (splitk > 1) {
     long long total4 = (long long)p.M * p.N / 4;
     hipLaunchKernelGGL(igemm_finalize_kernel, dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s, p);
@@ -257,17 +276,17 @@ bool igemm_mfma_supported(const IgemmParams& p) {
   if (p.epilogue == EPI_GEGLU && p.N % 128) return false;
   if (p.epilogue == EPI_SILU) return false;
   if (p.splitk > 1 && p.epilogue != EPI_NONE) return false;
+  // the kernel addresses activations and weights with 32-bit byte offsets
+  const long long samples = (p.M + (long long)p.Hout * p.Wout - 1) / ((long long)p.Hout * p.Wout);
+  const long long cmax = p.C1 > p.C2 ? p.C1 : p.C2;
+  if (samples * p.Hin * p.Win * cmax * 2 >= (1LL << 32)) return false;
+  if ((long long)p.N * p.K * 2 >= (1LL << 32)) return false;
   return true;
 }
 
 void launch_igemm_mfma(const IgemmParams& p, hipStream_t s) {
-  const bool k64 = (p.C1 % 64 == 0) && (p.C2 % 64 == 0);
-  int bn;
-  if (p.epilogue == EPI_GEGLU) bn = 128;
-  else if (p.N % 160 == 0) bn = 160;
-  else if (p.N % 128 == 0) bn = 128;
-  else bn = 64;
-  if (bn == 160) { if (k64) launch_cfg<128, 160, 2>(p, s); else launch_cfg<128, 160, 1>(p, s); }
-  else if (bn == 128) { if (k64) launch_cfg<128, 128, 2>(p, s); else launch_cfg<128, 128, 1>(p, s); }
-  else { if (k64) launch_cfg<128, 64, 2>(p, s); else launch_cfg<128, 64, 1>(p, s); }
+  if (p.epilogue == EPI_GEGLU) launch_cfg<128, 128>(p, s);
+  else if (p.N % 160 == 0) launch_cfg<128, 160>(p, s);
+  else if (p.N % 128 == 0) launch_cfg<128, 128>(p, s);
+  else launch_cfg<128, 64>(p, s);
 }
