@@ -13,6 +13,8 @@
 // turns into the output.
 #include "common.h"
 
+#include <stdlib.h>
+
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -253,8 +255,7 @@ __global__ __launch_bounds__(256) void igemm_finalize_kernel(IgemmParams p) {
   *(bf16x4*)((bf16_t*)p.out + e) = o;
 }
 
-template <int BM, int BN> void launch_cfg(const IgemmParams& p, hipStream_t s) {
-  constexpr int NSETS = 3;
+template <int BM, int BN, int NSETS> void launch_cfg(const IgemmParams& p, hipStream_t s) {
   const int mtiles = (p.M + BM - 1) / BM, ntiles = (p.N + BN - 1) / BN;
   const int ksteps_total = p.K / 32;
   const int splitk = p.splitk > 1 ? p.splitk : 1;
@@ -264,6 +265,17 @@ template <int BM, int BN> void launch_cfg(const IgemmParams& p, hipStream_t s) {
   if (splitk > 1) {
     long long total4 = (long long)p.M * p.N / 4;
     hipLaunchKernelGGL(igemm_finalize_kernel, dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s, p);
+  }
+}
+
+template <int BN> void launch_bn(const IgemmParams& p, hipStream_t s) {
+  static const int nsets = getenv("SDSTREAM_NSETS") ? atoi(getenv("SDSTREAM_NSETS")) : 3;
+  static const int bm64_below = getenv("SDSTREAM_BM64_BELOW") ? atoi(getenv("SDSTREAM_BM64_BELOW")) : 0;
+  const int tiles128 = ((p.M + 127) / 128) * ((p.N + BN - 1) / BN) * (p.splitk > 1 ? p.splitk : 1);
+  if (tiles128 < bm64_below) {
+    if (nsets == 4) launch_cfg<64, BN, 4>(p, s); else launch_cfg<64, BN, 3>(p, s);
+  } else {
+    if (nsets == 4) launch_cfg<128, BN, 4>(p, s); else launch_cfg<128, BN, 3>(p, s);
   }
 }
 
@@ -285,8 +297,8 @@ bool igemm_mfma_supported(const IgemmParams& p) {
 }
 
 void launch_igemm_mfma(const IgemmParams& p, hipStream_t s) {
-  if (p.epilogue == EPI_GEGLU) launch_cfg<128, 128>(p, s);
-  else if (p.N % 160 == 0) launch_cfg<128, 160>(p, s);
-  else if (p.N % 128 == 0) launch_cfg<128, 128>(p, s);
-  else launch_cfg<128, 64>(p, s);
+  if (p.epilogue == EPI_GEGLU) launch_bn<128>(p, s);
+  else if (p.N % 160 == 0) launch_bn<160>(p, s);
+  else if (p.N % 128 == 0) launch_bn<128>(p, s);
+  else launch_bn<64>(p, s);
 }
