@@ -38,6 +38,7 @@ struct IgemmParams {
   const void* zeros;     // MFMA kernel only: >= 16 readable zero bytes (source of padded / out-of-range rows)
 };
 
+#define GN_MAX_SPLIT 512
 struct GroupNormParams {
   const void* src1;
   const void* src2;
@@ -46,7 +47,8 @@ struct GroupNormParams {
   int silu;
   const float* gamma;
   const float* beta;
-  float* stats;  // [samples*groups][2] scratch: mean, rstd
+  float* stats;  // scratch, [samples][GN_MAX_SPLIT][groups][2] floats: partial sums, or mean / rstd per (sample, group)
+  float* meanrstd;  // [samples][groups][2]
   void* out;     // [samples][HW][C1+C2]
 };
 

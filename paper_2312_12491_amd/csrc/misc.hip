@@ -6,30 +6,42 @@
 namespace {
 
 // ---------------------------------------------------------------- conv_in
+// A block computes 64 pixels x all output channels: the 3x3xCin patches and the transposed weights sit in LDS.
+constexpr int CI_PIX = 64;
 template <typename T>
 __global__ __launch_bounds__(256) void conv_in_kernel(const float* __restrict__ x, const float* __restrict__ w,
                                                       const float* __restrict__ b, T* __restrict__ out, int N, int Cin,
                                                       int H, int W, int C0) {
-  long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  long long total = (long long)N * H * W * C0;
-  if (i >= total) return;
-  int co = (int)(i % C0);
-  long long pix = i / C0;
-  int xx = (int)(pix % W);
-  int yy = (int)((pix / W) % H);
-  int n = (int)(pix / ((long long)W * H));
-  float acc = b[co];
-  for (int ci = 0; ci < Cin; ++ci)
-    for (int ky = 0; ky < 3; ++ky) {
-      int iy = yy + ky - 1;
-      if (iy < 0 || iy >= H) continue;
-      for (int kx = 0; kx < 3; ++kx) {
-        int ix = xx + kx - 1;
-        if (ix < 0 || ix >= W) continue;
-        acc = fmaf(w[((co * Cin + ci) * 3 + ky) * 3 + kx], x[(((long long)n * Cin + ci) * H + iy) * W + ix], acc);
-      }
+  extern __shared__ float sm[];
+  const int K = Cin * 9;
+  float* wt = sm;               // [K][C0]
+  float* patch = sm + K * C0;   // [CI_PIX][K]
+  const long long total_pix = (long long)N * H * W;
+  const long long pix0 = (long long)blockIdx.x * CI_PIX;
+  for (int i = threadIdx.x; i < K * C0; i += 256) {
+    int co = i / K, k = i - co * K;  // global read is contiguous (OIHW = [co][k])
+    wt[k * C0 + co] = w[i];
+  }
+  for (int i = threadIdx.x; i < CI_PIX * K; i += 256) {
+    int p = i / K, k = i - p * K;
+    long long pix = pix0 + p;
+    float v = 0.f;
+    if (pix < total_pix) {
+      int xx = (int)(pix % W), yy = (int)((pix / W) % H), n = (int)(pix / ((long long)W * H));
+      int ci = k / 9, t = k - ci * 9;
+      int iy = yy + t / 3 - 1, ix = xx + t % 3 - 1;
+      if (iy >= 0 && iy < H && ix >= 0 && ix < W) v = x[(((long long)n * Cin + ci) * H + iy) * W + ix];
     }
-  out[i] = from_f32<T>(acc);
+    patch[i] = v;
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < CI_PIX * C0; i += 256) {
+    int p = i / C0, co = i - p * C0;
+    if (pix0 + p >= total_pix) break;
+    float acc = b[co];
+    for (int k = 0; k < K; ++k) acc = fmaf(wt[k * C0 + co], patch[p * K + k], acc);
+    out[(pix0 + p) * C0 + co] = from_f32<T>(acc);
+  }
 }
 
 // ---------------------------------------------------------------- conv_out: one wave per output pixel
@@ -249,9 +261,10 @@ inline unsigned blocks_for(long long n, int per = 256, long long cap = 1 << 20) 
 template <typename T>
 void launch_conv_in(const float* x, const float* w, const float* b, void* out, int N, int Cin, int H, int W, int C0,
                     hipStream_t s) {
-  long long total = (long long)N * H * W * C0;
-  hipLaunchKernelGGL(conv_in_kernel<T>, dim3(blocks_for(total, 256, 1LL << 31)), dim3(256), 0, s, x, w, b, (T*)out, N,
-                     Cin, H, W, C0);
+  long long pix = (long long)N * H * W;
+  size_t lds = (size_t)(Cin * 9 * C0 + CI_PIX * Cin * 9) * sizeof(float);
+  hipLaunchKernelGGL(conv_in_kernel<T>, dim3((unsigned)((pix + CI_PIX - 1) / CI_PIX)), dim3(256), lds, s, x, w, b,
+                     (T*)out, N, Cin, H, W, C0);
 }
 template void launch_conv_in<float>(const float*, const float*, const float*, void*, int, int, int, int, int, hipStream_t);
 template void launch_conv_in<bf16_t>(const float*, const float*, const float*, void*, int, int, int, int, int, hipStream_t);

@@ -89,20 +89,210 @@ __global__ __launch_bounds__(256) void layer_norm_kernel(LayerNormParams p) {
     y[c] = from_f32<T>((to_f32<T>(x[c]) - mean) * rstd * p.gamma[c] + p.beta[c]);
 }
 
+// ---------------------------------------------------------------------------------------------------
+// bf16 fast path.  A block owns PPB pixels of one sample and all channels; a thread owns one 16-byte
+// chunk (8 channels) and walks the pixels with its row of lanes, so every global access is a full
+// coalesced row.  Pass 1 writes per-(sample, pixel-split, group) partial sums in a fixed order
+// (deterministic); pass 2 folds the partials in double, then normalises, scales and applies SiLU.
+// ---------------------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+
+__device__ __forceinline__ bf16x8 gn_load8(const GroupNormParams& p, long long pix, int c) {
+  const bf16_t* src = c < p.C1 ? (const bf16_t*)p.src1 + pix * p.C1 + c : (const bf16_t*)p.src2 + pix * p.C2 + (c - p.C1);
+  return *(const bf16x8*)src;
+}
+
+__global__ void gn_partial_bf16_kernel(GroupNormParams p, int ppb, int nsplit, int chunks, int lanes) {
+  extern __shared__ float sm[];  // [lanes][C][2]
+  const int C = p.C1 + p.C2, cg = C / p.groups;
+  const int n = blockIdx.x / nsplit, sp = blockIdx.x - n * nsplit;
+  const int chunk = threadIdx.x % chunks, ln = threadIdx.x / chunks;
+  const int px0 = sp * ppb, px1 = min(p.HW, px0 + ppb);
+  float s[8], q[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { s[e] = 0.f; q[e] = 0.f; }
+  for (int px = px0 + ln; px < px1; px += lanes) {
+    bf16x8 v = gn_load8(p, (long long)n * p.HW + px, chunk * 8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float x = (float)v[e];
+      s[e] += x;
+      q[e] = fmaf(x, x, q[e]);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    sm[(ln * C + chunk * 8 + e) * 2] = s[e];
+    sm[(ln * C + chunk * 8 + e) * 2 + 1] = q[e];
+  }
+  __syncthreads();
+  for (int g = threadIdx.x; g < p.groups; g += blockDim.x) {
+    float ss = 0.f, qq = 0.f;
+    for (int l = 0; l < lanes; ++l)
+      for (int c = g * cg; c < (g + 1) * cg; ++c) {
+        ss += sm[(l * C + c) * 2];
+        qq += sm[(l * C + c) * 2 + 1];
+      }
+    float* dst = p.stats + (((long long)n * nsplit + sp) * p.groups + g) * 2;
+    dst[0] = ss;
+    dst[1] = qq;
+  }
+}
+
+// one wave per (sample, group): folds the pixel-split partials in double, fixed order
+__global__ __launch_bounds__(256) void gn_finalize_kernel(GroupNormParams p, int nsplit) {
+  const int idx = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (idx >= p.samples * p.groups) return;
+  const int n = idx / p.groups, g = idx - n * p.groups;
+  const int cg = (p.C1 + p.C2) / p.groups;
+  double ss = 0.0, qq = 0.0;
+  for (int k = lane; k < nsplit; k += 64) {
+    const float* src = p.stats + (((long long)n * nsplit + k) * p.groups + g) * 2;
+    ss += src[0];
+    qq += src[1];
+  }
+  ss = wave_sum(ss);
+  qq = wave_sum(qq);
+  if (lane == 0) {
+    const double cnt = (double)p.HW * cg;
+    const double mean = ss / cnt;
+    double var = qq / cnt - mean * mean;
+    if (var < 0) var = 0;
+    p.meanrstd[idx * 2] = (float)mean;
+    p.meanrstd[idx * 2 + 1] = (float)(1.0 / sqrt(var + (double)p.eps));
+  }
+}
+
+__global__ void gn_apply_bf16_kernel(GroupNormParams p, int ppb, int nsplit, int chunks, int lanes) {
+  extern __shared__ float sm[];  // [groups][2]: mean, rstd
+  const int C = p.C1 + p.C2, cg = C / p.groups;
+  const int n = blockIdx.x / nsplit, sp = blockIdx.x - n * nsplit;
+  const int chunk = threadIdx.x % chunks, ln = threadIdx.x / chunks;
+  for (int i = threadIdx.x; i < p.groups * 2; i += blockDim.x) sm[i] = p.meanrstd[(long long)n * p.groups * 2 + i];
+  __syncthreads();
+  float sc[8], sh[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int c = chunk * 8 + e, g = c / cg;
+    const float rs = sm[g * 2 + 1] * p.gamma[c];
+    sc[e] = rs;
+    sh[e] = p.beta[c] - sm[g * 2] * rs;
+  }
+  const int px0 = sp * ppb, px1 = min(p.HW, px0 + ppb);
+  bf16_t* out = (bf16_t*)p.out;
+  for (int px = px0 + ln; px < px1; px += lanes) {
+    const long long pix = (long long)n * p.HW + px;
+    bf16x8 v = gn_load8(p, pix, chunk * 8), o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float y = fmaf((float)v[e], sc[e], sh[e]);
+      if (p.silu) y = y / (1.0f + __expf(-y));
+      o[e] = (bf16_t)y;
+    }
+    *(bf16x8*)(out + pix * C + chunk * 8) = o;
+  }
+}
+
+bool gn_fast_ok(const GroupNormParams& p) {
+  const int C = p.C1 + p.C2;
+  return p.C1 % 8 == 0 && p.C2 % 8 == 0 && C / 8 <= 1024;
+}
+
+void launch_gn_fast(const GroupNormParams& p, hipStream_t s) {
+  const int C = p.C1 + p.C2, chunks = C / 8;
+  const int lanes = chunks >= 256 ? 1 : 256 / chunks;
+  const int threads = chunks * lanes;
+  long long want = ((long long)p.HW * p.samples + 1023) / 1024;  // aim for ~1024 blocks
+  int ppb = (int)(want < 2 * lanes ? 2 * lanes : want);
+  if (ppb > 64) ppb = 64;
+  int nsplit = (p.HW + ppb - 1) / ppb;
+  if (nsplit > GN_MAX_SPLIT) { nsplit = GN_MAX_SPLIT; ppb = (p.HW + nsplit - 1) / nsplit; nsplit = (p.HW + ppb - 1) / ppb; }
+  const dim3 grid(p.samples * nsplit);
+  hipLaunchKernelGGL(gn_partial_bf16_kernel, grid, dim3(threads), (size_t)lanes * C * 2 * sizeof(float), s, p, ppb, nsplit,
+                     chunks, lanes);
+  hipLaunchKernelGGL(gn_finalize_kernel, dim3((p.samples * p.groups + 3) / 4), dim3(256), 0, s, p, nsplit);
+  hipLaunchKernelGGL(gn_apply_bf16_kernel, grid, dim3(threads), (size_t)p.groups * 2 * sizeof(float), s, p, ppb, nsplit,
+                     chunks, lanes);
+}
+
 }  // namespace
 
-template <typename T> void launch_group_norm(const GroupNormParams& p, hipStream_t s) {
+template <typename T> void launch_group_norm_generic(const GroupNormParams& p, hipStream_t s);
+
+template <typename T> void launch_group_norm(const GroupNormParams& p, hipStream_t s) { launch_group_norm_generic<T>(p, s); }
+template <> void launch_group_norm<bf16_t>(const GroupNormParams& p, hipStream_t s) {
+  if (gn_fast_ok(p)) launch_gn_fast(p, s); else launch_group_norm_generic<bf16_t>(p, s);
+}
+template void launch_group_norm<float>(const GroupNormParams&, hipStream_t);
+
+template <typename T> void launch_group_norm_generic(const GroupNormParams& p, hipStream_t s) {
   hipLaunchKernelGGL(gn_stats_kernel<T>, dim3(p.samples * p.groups), dim3(256), 0, s, p);
   long long total = (long long)p.samples * p.HW * (p.C1 + p.C2);
   long long blocks = (total + 255) / 256;
   if (blocks > 65536) blocks = 65536;
   hipLaunchKernelGGL(gn_apply_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, p, total);
 }
-template void launch_group_norm<float>(const GroupNormParams&, hipStream_t);
-template void launch_group_norm<bf16_t>(const GroupNormParams&, hipStream_t);
+template void launch_group_norm_generic<float>(const GroupNormParams&, hipStream_t);
+template void launch_group_norm_generic<bf16_t>(const GroupNormParams&, hipStream_t);
+
+namespace {
+// bf16 fast path: a wave owns a row and keeps it in registers (16-byte chunks, up to 3 per lane: C <= 1536)
+__global__ __launch_bounds__(256) void layer_norm_bf16_kernel(LayerNormParams p) {
+  typedef __attribute__((ext_vector_type(8))) __bf16 v8;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= p.rows) return;
+  const int chunks = p.C >> 3;
+  const bf16_t* x = (const bf16_t*)p.src + (long long)row * p.C;
+  bf16_t* y = (bf16_t*)p.out + (long long)row * p.C;
+  v8 v[3];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 3; ++i) {
+    const int ch = lane + i * 64;
+    if (ch < chunks) {
+      v[i] = *(const v8*)(x + ch * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sum += (float)v[i][e];
+    }
+  }
+  const float mean = wave_sum(sum) / (float)p.C;
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < 3; ++i) {
+    const int ch = lane + i * 64;
+    if (ch < chunks) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float d = (float)v[i][e] - mean;
+        sq = fmaf(d, d, sq);
+      }
+    }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)p.C + p.eps);
+#pragma unroll
+  for (int i = 0; i < 3; ++i) {
+    const int ch = lane + i * 64;
+    if (ch < chunks) {
+      v8 o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        o[e] = (bf16_t)(((float)v[i][e] - mean) * rstd * p.gamma[ch * 8 + e] + p.beta[ch * 8 + e]);
+      *(v8*)(y + ch * 8) = o;
+    }
+  }
+}
+}  // namespace
+
+template <> void launch_layer_norm<bf16_t>(const LayerNormParams& p, hipStream_t s);
 
 template <typename T> void launch_layer_norm(const LayerNormParams& p, hipStream_t s) {
   hipLaunchKernelGGL(layer_norm_kernel<T>, dim3((p.rows + 3) / 4), dim3(256), 0, s, p);
 }
 template void launch_layer_norm<float>(const LayerNormParams&, hipStream_t);
-template void launch_layer_norm<bf16_t>(const LayerNormParams&, hipStream_t);
+template <> void launch_layer_norm<bf16_t>(const LayerNormParams& p, hipStream_t s) {
+  if (p.C % 8 == 0 && p.C <= 1536)
+    hipLaunchKernelGGL(layer_norm_bf16_kernel, dim3((p.rows + 3) / 4), dim3(256), 0, s, p);
+  else
+    hipLaunchKernelGGL(layer_norm_kernel<bf16_t>, dim3((p.rows + 3) / 4), dim3(256), 0, s, p);
+}
