@@ -26,6 +26,67 @@ __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + e
 
 template <int I> struct IC { static constexpr int value = I; };
 
+// Epilogue shared by the kernels: lane holds channels n..n+3 (n = (gnt0+nt)*16 + 4*(lane/16)) of pixel
+// m = mbase + mt*16 + lane%16 in acc[mt][nt].
+template <int MT, int NT>
+__device__ __forceinline__ void epilogue(const IgemmParams& p, f32x4 (&acc)[MT][NT], int mbase, int gnt0, int lane,
+                                         int HWo) {
+  const int Nout = p.epilogue == EPI_GEGLU ? p.N >> 1 : p.N;
+  bf16_t* out = (bf16_t*)p.out;
+  const bf16_t* res = (const bf16_t*)p.residual;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    const int m = mbase + mt * 16 + (lane & 15);
+    if (m >= p.M) continue;
+    const int sample = m / HWo;
+    if (p.splitk > 1) {
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const int n = (gnt0 + nt) * 16 + (lane >> 4) * 4;
+        if (n >= p.N) continue;
+        *(f32x4*)(p.workspace + ((long long)blockIdx.z * p.M + m) * p.N + n) = acc[mt][nt];
+      }
+      continue;
+    }
+    if (p.epilogue == EPI_GEGLU) {
+#pragma unroll
+      for (int nt = 0; nt < NT; nt += 2) {
+        const int n = (gnt0 + nt) * 16 + (lane >> 4) * 4;
+        if (n >= p.N) continue;
+        f32x4 a = acc[mt][nt], g = acc[mt][nt + 1];
+        if (p.bias) {
+          a += *(const f32x4*)(p.bias + n);
+          g += *(const f32x4*)(p.bias + n + 16);
+        }
+        bf16x4 o;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) o[v] = (bf16_t)(a[v] * gelu_erf(g[v]));
+        const int oc = ((gnt0 + nt) >> 1) * 16 + (lane >> 4) * 4;
+        *(bf16x4*)(out + (long long)m * Nout + oc) = o;
+      }
+    } else {
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const int n = (gnt0 + nt) * 16 + (lane >> 4) * 4;
+        if (n >= p.N) continue;
+        f32x4 x = acc[mt][nt];
+        if (p.bias) x += *(const f32x4*)(p.bias + n);
+        if (p.rowbias) x += *(const f32x4*)(p.rowbias + (long long)sample * p.rowbias_ld + n);
+        if (res) {
+          bf16x4 r = *(const bf16x4*)(res + (long long)m * Nout + n);
+#pragma unroll
+          for (int v = 0; v < 4; ++v) x[v] += (float)r[v];
+        }
+        bf16x4 o;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) o[v] = (bf16_t)x[v];
+        *(bf16x4*)(out + (long long)m * Nout + n) = o;
+      }
+    }
+  }
+}
+
+
 template <int BM, int BN, int NSETS>
 __global__ __launch_bounds__(256, 2) void igemm_mfma_kernel(IgemmParams p, int mtiles, int ksteps_total,
                                                          int stages_per_split) {
@@ -177,60 +238,364 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma_kernel(IgemmParams p, int m
     }
   }
 
-  // ---- epilogue: lane holds channels n..n+3 of pixel m
-  const int Nout = p.epilogue == EPI_GEGLU ? p.N >> 1 : p.N;
-  bf16_t* out = (bf16_t*)p.out;
-  const bf16_t* res = (const bf16_t*)p.residual;
+  epilogue<MT, NT>(p, acc, m0 + wm * WTM, gnt0, lane, HWo);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Variant for channel counts that are multiples of 64: 64-deep K stages, BOTH operands through LDS.
+// Each weight fragment is fetched from global memory once per block (not once per wave row), which
+// is what bounds the other variant: the vector L1 delivers far fewer bytes per clock than the matrix
+// cores can consume.  Weights keep their fragment-packed global layout, so a block's slice of a stage
+// is BN/16 contiguous 2 KB runs that land in LDS in fragment order (conflict-free 16-byte reads).
+// ---------------------------------------------------------------------------------------------------
+template <int BM, int BN>
+__global__ __launch_bounds__(256, 2) void igemm_mfma64_kernel(IgemmParams p, int mtiles, int ksteps_total,
+                                                              int stages_per_split) {
+  constexpr int WM = 2, WN = 2;
+  constexpr int WTM = BM / WM, WTN = BN / WN, MT = WTM / 16, NT = WTN / 16;
+  constexpr int ROWB = 144;               // A row pitch: 64 bf16 + 16 bytes pad
+  constexpr int NLA = BM * 8 / 256;       // 16-byte chunks of A per thread and stage
+  constexpr int NLB = BN * 8 / 256;       // 16-byte chunks of B per thread and stage
+  constexpr int ABYTES = BM * ROWB, BBYTES = BN * 128, STAGE = ABYTES + BBYTES;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // 2 stages of [A | B]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave & 1, wn = wave >> 1;
+  const int mtile = blockIdx.x % mtiles, ntile = blockIdx.x / mtiles;
+  const int m0 = mtile * BM, n0 = ntile * BN;
+  const int Ct = p.C1 + p.C2;
+  const int pad = p.ksize >> 1;
+  const int HWo = p.Hout * p.Wout;
+  const int Hs = p.upsample ? p.Hin * 2 : p.Hin, Wsz = p.upsample ? p.Win * 2 : p.Win;
+  const int ups = p.upsample;
+  const char* s1 = (const char*)p.src1;
+  const char* s2 = (const char*)p.src2;
+  const char* Wp = (const char*)p.W;
+
+  int ld_y[NLA], ld_x[NLA], ld_lds[NLA];
+  unsigned ld_pix0[NLA];
+  bool ld_ok[NLA];
+  const int cq = tid & 7;
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    const int m = m0 + wm * WTM + mt * 16 + (lane & 15);
-    if (m >= p.M) continue;
-    const int sample = m / HWo;
-    if (p.splitk > 1) {
+  for (int i = 0; i < NLA; ++i) {
+    int row = (tid + i * 256) >> 3;
+    ld_lds[i] = row * ROWB + cq * 16;
+    int m = m0 + row;
+    ld_ok[i] = m < p.M;
+    int mm = ld_ok[i] ? m : 0;
+    int n = mm / HWo;
+    int r = mm - n * HWo;
+    int oy = r / p.Wout, ox = r - oy * p.Wout;
+    ld_y[i] = oy * p.stride - pad;
+    ld_x[i] = ox * p.stride - pad;
+    ld_pix0[i] = (unsigned)n * (unsigned)(p.Hin * p.Win);
+  }
+  // B chunks of this thread: chunk q = tid + i*256 -> n-tile q/128, position q%128 inside the 2 KB run
+  const int gnt_blk = n0 >> 4, ntiles_total = p.N >> 4;
+  unsigned boff[NLB];
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        const int n = (gnt0 + nt) * 16 + (lane >> 4) * 4;
-        if (n >= p.N) continue;
-        *(f32x4*)(p.workspace + ((long long)blockIdx.z * p.M + m) * p.N + n) = acc[mt][nt];
-      }
-      continue;
+  for (int i = 0; i < NLB; ++i) {
+    int q = tid + i * 256;
+    int g = gnt_blk + (q >> 7);
+    if (g >= ntiles_total) g = ntiles_total - 1;
+    boff[i] = ((unsigned)g * (unsigned)ksteps_total * 64u + (unsigned)(q & 127)) * 16u;
+  }
+
+  const int total_stages = ksteps_total >> 1;
+  const int stage0 = blockIdx.z * stages_per_split;
+  int nstages = total_stages - stage0;
+  if (nstages > stages_per_split) nstages = stages_per_split;
+  int l_stage = stage0;
+  const int stage_last = total_stages - 1;
+  int l_c, l_ky, l_kx;
+  {
+    int kk = stage0 * 64;
+    int tap = kk / Ct;
+    l_c = kk - tap * Ct;
+    l_ky = tap / p.ksize;
+    l_kx = tap - l_ky * p.ksize;
+  }
+
+  u32x4 areg[2][NLA], breg[2][NLB];
+  unsigned okm[2];
+  auto load = [&](auto setc) {
+    constexpr int set = decltype(setc)::value;
+    const char* src;
+    int Cs, c = l_c;
+    if (c < p.C1) { src = s1; Cs = p.C1; } else { src = s2; Cs = p.C2; c -= p.C1; }
+    unsigned m = 0;
+#pragma unroll
+    for (int i = 0; i < NLA; ++i) {
+      int iy = ld_y[i] + l_ky, ix = ld_x[i] + l_kx;
+      bool ok = ld_ok[i] && (unsigned)iy < (unsigned)Hs && (unsigned)ix < (unsigned)Wsz;
+      iy = min(max(iy, 0), Hs - 1) >> ups;
+      ix = min(max(ix, 0), Wsz - 1) >> ups;
+      unsigned off = ((ld_pix0[i] + (unsigned)(iy * p.Win + ix)) * (unsigned)Cs + (unsigned)(c + cq * 8)) * 2u;
+#ifdef IGEMM_NO_GLOBAL
+      areg[set][i] = u32x4{off, off, off, off};
+#else
+      areg[set][i] = *(const u32x4*)(src + off);
+#endif
+      m |= (ok ? 1u : 0u) << i;
     }
-    if (p.epilogue == EPI_GEGLU) {
+    okm[set] = m;
+    const unsigned kb = (unsigned)min(l_stage, stage_last) * 2048u;
 #pragma unroll
-      for (int nt = 0; nt < NT; nt += 2) {
-        const int n = (gnt0 + nt) * 16 + (lane >> 4) * 4;
-        if (n >= p.N) continue;
-        f32x4 a = acc[mt][nt], g = acc[mt][nt + 1];
-        if (p.bias) {
-          a += *(const f32x4*)(p.bias + n);
-          g += *(const f32x4*)(p.bias + n + 16);
-        }
-        bf16x4 o;
+#ifdef IGEMM_NO_GLOBAL
+    for (int i = 0; i < NLB; ++i) breg[set][i] = u32x4{kb, kb, kb, boff[i]};
+#else
+    for (int i = 0; i < NLB; ++i) breg[set][i] = *(const u32x4*)(Wp + (boff[i] + kb));
+#endif
+    ++l_stage;
+    l_c += 64;
+    if (l_c >= Ct) {
+      l_c = 0;
+      if (++l_kx == p.ksize) { l_kx = 0; ++l_ky; }
+    }
+  };
+
+  f32x4 acc[MT][NT];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) o[v] = (bf16_t)(a[v] * gelu_erf(g[v]));
-        const int oc = ((gnt0 + nt) >> 1) * 16 + (lane >> 4) * 4;
-        *(bf16x4*)(out + (long long)m * Nout + oc) = o;
-      }
-    } else {
+  for (int i = 0; i < MT; ++i)
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        const int n = (gnt0 + nt) * 16 + (lane >> 4) * 4;
-        if (n >= p.N) continue;
-        f32x4 x = acc[mt][nt];
-        if (p.bias) x += *(const f32x4*)(p.bias + n);
-        if (p.rowbias) x += *(const f32x4*)(p.rowbias + (long long)sample * p.rowbias_ld + n);
-        if (res) {
-          bf16x4 r = *(const bf16x4*)(res + (long long)m * Nout + n);
+    for (int j = 0; j < NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  int buf = 0;
+  auto stage = [&](auto setc) {
+    constexpr int set = decltype(setc)::value;
+    unsigned char* sa = lds + buf * STAGE;
+    unsigned char* sb = sa + ABYTES;
 #pragma unroll
-          for (int v = 0; v < 4; ++v) x[v] += (float)r[v];
-        }
-        bf16x4 o;
+    for (int i = 0; i < NLA; ++i) {
+      u32x4 v = areg[set][i];
+      if (!((okm[set] >> i) & 1u)) v = u32x4{0u, 0u, 0u, 0u};
+#ifndef IGEMM_NO_LDSWRITE
+      *(u32x4*)(sa + ld_lds[i]) = v;
+#else
+      if (v[0] == 0x12345u) *(u32x4*)(sa + ld_lds[i]) = v;
+#endif
+    }
 #pragma unroll
-        for (int v = 0; v < 4; ++v) o[v] = (bf16_t)x[v];
-        *(bf16x4*)(out + (long long)m * Nout + n) = o;
-      }
+    for (int i = 0; i < NLB; ++i) {
+#ifndef IGEMM_NO_LDSWRITE
+      *(u32x4*)(sb + (tid + i * 256) * 16) = breg[set][i];
+#else
+      if (breg[set][i][0] == 0x12345u) *(u32x4*)(sb + (tid + i * 256) * 16) = breg[set][i];
+#endif
+    }
+#ifndef IGEMM_NO_BARRIER
+    __syncthreads();
+#endif
+    load(IC<set ^ 1>{});
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      bf16x8 af[MT], bfr[NT];
+#pragma unroll
+#ifdef IGEMM_NO_LDSREAD
+      for (int mt = 0; mt < MT; ++mt) for (int e = 0; e < 8; ++e) af[mt][e] = (bf16_t)(float)(lane + mt + buf);
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) for (int e = 0; e < 8; ++e) bfr[nt][e] = (bf16_t)(float)(lane + nt + buf);
+#else
+      for (int mt = 0; mt < MT; ++mt)
+        af[mt] = *(const bf16x8*)(sa + (wm * WTM + mt * 16 + (lane & 15)) * ROWB + ks * 64 + (lane >> 4) * 16);
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) bfr[nt] = *(const bf16x8*)(sb + ((wn * NT + nt) * 2 + ks) * 1024 + lane * 16);
+#endif
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#ifdef IGEMM_NO_MFMA
+          acc[mt][nt][0] += (float)bfr[nt][0] * (float)af[mt][0];
+#else
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[nt], af[mt], acc[mt][nt], 0, 0, 0);
+#endif
+    }
+    buf ^= 1;
+  };
+
+  load(IC<0>{});
+  for (int base = 0; base < nstages; base += 2) {
+    stage(IC<0>{});
+    if (base + 1 >= nstages) break;
+    stage(IC<1>{});
+  }
+  epilogue<MT, NT>(p, acc, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// 8-wave variant of the kernel above for grids that give a compute unit only one block.  One wave per
+// SIMD cannot issue v_mfma_f32_16x16x32_bf16 back to back (measured: 58 % of peak with 20 independent
+// accumulators, 93 % with two waves), so the block carries two wave groups that split every 64-deep
+// stage between them (k 0..31 / k 32..63 of the same 128 x BN tile) and add their accumulators through
+// LDS at the end.  Tile, traffic and LDS layout are those of the 4-wave kernel.
+// ---------------------------------------------------------------------------------------------------
+template <int BM, int BN>
+__global__ __launch_bounds__(512) void igemm_mfma64x8_kernel(IgemmParams p, int mtiles, int ksteps_total,
+                                                             int stages_per_split) {
+  constexpr int WM = 2, WN = 2;
+  constexpr int WTM = BM / WM, WTN = BN / WN, MT = WTM / 16, NT = WTN / 16;
+  constexpr int ROWB = 144;
+  constexpr int NLA = BM * 8 / 512;
+  constexpr int NBCH = BN * 8;                 // 16-byte chunks of B per stage
+  constexpr int NLB = (NBCH + 511) / 512;
+  constexpr int ABYTES = BM * ROWB, BBYTES = BN * 128, STAGE = ABYTES + BBYTES;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kgrp = wave >> 2, wm = wave & 1, wn = (wave >> 1) & 1;
+  const int mtile = blockIdx.x % mtiles, ntile = blockIdx.x / mtiles;
+  const int m0 = mtile * BM, n0 = ntile * BN;
+  const int Ct = p.C1 + p.C2;
+  const int pad = p.ksize >> 1;
+  const int HWo = p.Hout * p.Wout;
+  const int Hs = p.upsample ? p.Hin * 2 : p.Hin, Wsz = p.upsample ? p.Win * 2 : p.Win;
+  const int ups = p.upsample;
+  const char* s1 = (const char*)p.src1;
+  const char* s2 = (const char*)p.src2;
+  const char* Wp = (const char*)p.W;
+
+  int ld_y[NLA], ld_x[NLA], ld_lds[NLA];
+  unsigned ld_pix0[NLA];
+  bool ld_ok[NLA];
+  const int cq = tid & 7;
+#pragma unroll
+  for (int i = 0; i < NLA; ++i) {
+    int row = (tid + i * 512) >> 3;
+    ld_lds[i] = row * ROWB + cq * 16;
+    int m = m0 + row;
+    ld_ok[i] = m < p.M;
+    int mm = ld_ok[i] ? m : 0;
+    int n = mm / HWo;
+    int r = mm - n * HWo;
+    int oy = r / p.Wout, ox = r - oy * p.Wout;
+    ld_y[i] = oy * p.stride - pad;
+    ld_x[i] = ox * p.stride - pad;
+    ld_pix0[i] = (unsigned)n * (unsigned)(p.Hin * p.Win);
+  }
+  const int gnt_blk = n0 >> 4, ntiles_total = p.N >> 4;
+  unsigned boff[NLB];
+#pragma unroll
+  for (int i = 0; i < NLB; ++i) {
+    int q = tid + i * 512;
+    if (q >= NBCH) q = NBCH - 1;  // surplus lanes repeat the last chunk (same value, same address)
+    int g = gnt_blk + (q >> 7);
+    if (g >= ntiles_total) g = ntiles_total - 1;
+    boff[i] = ((unsigned)g * (unsigned)ksteps_total * 64u + (unsigned)(q & 127)) * 16u;
+  }
+
+  const int total_stages = ksteps_total >> 1;
+  const int stage0 = blockIdx.z * stages_per_split;
+  int nstages = total_stages - stage0;
+  if (nstages > stages_per_split) nstages = stages_per_split;
+  int l_stage = stage0;
+  const int stage_last = total_stages - 1;
+  int l_c, l_ky, l_kx;
+  {
+    int kk = stage0 * 64;
+    int tap = kk / Ct;
+    l_c = kk - tap * Ct;
+    l_ky = tap / p.ksize;
+    l_kx = tap - l_ky * p.ksize;
+  }
+
+  u32x4 areg[2][NLA], breg[2][NLB];
+  unsigned okm[2];
+  auto load = [&](auto setc) {
+    constexpr int set = decltype(setc)::value;
+    const char* src;
+    int Cs, c = l_c;
+    if (c < p.C1) { src = s1; Cs = p.C1; } else { src = s2; Cs = p.C2; c -= p.C1; }
+    unsigned m = 0;
+#pragma unroll
+    for (int i = 0; i < NLA; ++i) {
+      int iy = ld_y[i] + l_ky, ix = ld_x[i] + l_kx;
+      bool ok = ld_ok[i] && (unsigned)iy < (unsigned)Hs && (unsigned)ix < (unsigned)Wsz;
+      iy = min(max(iy, 0), Hs - 1) >> ups;
+      ix = min(max(ix, 0), Wsz - 1) >> ups;
+      unsigned off = ((ld_pix0[i] + (unsigned)(iy * p.Win + ix)) * (unsigned)Cs + (unsigned)(c + cq * 8)) * 2u;
+      areg[set][i] = *(const u32x4*)(src + off);
+      m |= (ok ? 1u : 0u) << i;
+    }
+    okm[set] = m;
+    const unsigned kb = (unsigned)min(l_stage, stage_last) * 2048u;
+#pragma unroll
+    for (int i = 0; i < NLB; ++i) breg[set][i] = *(const u32x4*)(Wp + (boff[i] + kb));
+    ++l_stage;
+    l_c += 64;
+    if (l_c >= Ct) {
+      l_c = 0;
+      if (++l_kx == p.ksize) { l_kx = 0; ++l_ky; }
+    }
+  };
+
+  f32x4 acc[MT][NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  int buf = 0;
+  auto stage = [&](auto setc) {
+    constexpr int set = decltype(setc)::value;
+    unsigned char* sa = lds + buf * STAGE;
+    unsigned char* sb = sa + ABYTES;
+#pragma unroll
+    for (int i = 0; i < NLA; ++i) {
+      u32x4 v = areg[set][i];
+      if (!((okm[set] >> i) & 1u)) v = u32x4{0u, 0u, 0u, 0u};
+      *(u32x4*)(sa + ld_lds[i]) = v;
+    }
+#pragma unroll
+    for (int i = 0; i < NLB; ++i) {
+      int q = tid + i * 512;
+      if (q >= NBCH) q = NBCH - 1;
+      *(u32x4*)(sb + q * 16) = breg[set][i];
+    }
+    __syncthreads();
+    load(IC<set ^ 1>{});
+    bf16x8 af[MT], bfr[NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+      af[mt] = *(const bf16x8*)(sa + (wm * WTM + mt * 16 + (lane & 15)) * ROWB + kgrp * 64 + (lane >> 4) * 16);
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) bfr[nt] = *(const bf16x8*)(sb + ((wn * NT + nt) * 2 + kgrp) * 1024 + lane * 16);
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[nt], af[mt], acc[mt][nt], 0, 0, 0);
+    buf ^= 1;
+  };
+
+  load(IC<0>{});
+  for (int base = 0; base < nstages; base += 2) {
+    stage(IC<0>{});
+    if (base + 1 >= nstages) break;
+    stage(IC<1>{});
+  }
+
+  // fold the second wave group into the first through LDS, two m-tiles at a time
+  static_assert(4 * (MT / 2) * NT * 1024 <= 2 * STAGE, "reduction buffer must fit in the stage buffers");
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    __syncthreads();
+    f32x4* red = (f32x4*)lds + ((wave & 3) * (MT / 2) * NT) * 64 + lane;
+    if (kgrp == 1) {
+#pragma unroll
+      for (int mt = 0; mt < MT / 2; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) red[(mt * NT + nt) * 64] = acc[half * (MT / 2) + mt][nt];
+    }
+    __syncthreads();
+    if (kgrp == 0) {
+#pragma unroll
+      for (int mt = 0; mt < MT / 2; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[half * (MT / 2) + mt][nt] += red[(mt * NT + nt) * 64];
     }
   }
+  if (kgrp == 0) epilogue<MT, NT>(p, acc, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo);
 }
 
 // split-K finalize: sum of the partials (fp32 [splitk][M][N]) -> out with the epilogue of the main kernel
@@ -268,7 +633,57 @@ template <int BM, int BN, int NSETS> void launch_cfg(const IgemmParams& p, hipSt
   }
 }
 
+template <int BM, int BN> void launch_cfg64(const IgemmParams& p, hipStream_t s) {
+  constexpr int LDS = 2 * (BM * 144 + BN * 128);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipFuncSetAttribute((const void*)igemm_mfma64_kernel<BM, BN>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    attr_set = true;
+  }
+  const int mtiles = (p.M + BM - 1) / BM, ntiles = (p.N + BN - 1) / BN;
+  const int ksteps_total = p.K / 32;
+  const int total_stages = ksteps_total / 2;
+  const int splitk = p.splitk > 1 ? p.splitk : 1;
+  const int sps = (total_stages + splitk - 1) / splitk;
+  dim3 grid(mtiles * ntiles, 1, splitk);
+  hipLaunchKernelGGL((igemm_mfma64_kernel<BM, BN>), grid, dim3(256), LDS, s, p, mtiles, ksteps_total, sps);
+  if (splitk > 1) {
+    long long total4 = (long long)p.M * p.N / 4;
+    hipLaunchKernelGGL(igemm_finalize_kernel, dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s, p);
+  }
+}
+
+template <int BM, int BN> void launch_cfg64x8(const IgemmParams& p, hipStream_t s) {
+  constexpr int LDS = 2 * (BM * 144 + BN * 128);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipFuncSetAttribute((const void*)igemm_mfma64x8_kernel<BM, BN>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    attr_set = true;
+  }
+  const int mtiles = (p.M + BM - 1) / BM, ntiles = (p.N + BN - 1) / BN;
+  const int ksteps_total = p.K / 32;
+  const int total_stages = ksteps_total / 2;
+  const int splitk = p.splitk > 1 ? p.splitk : 1;
+  const int sps = (total_stages + splitk - 1) / splitk;
+  dim3 grid(mtiles * ntiles, 1, splitk);
+  hipLaunchKernelGGL((igemm_mfma64x8_kernel<BM, BN>), grid, dim3(512), LDS, s, p, mtiles, ksteps_total, sps);
+  if (splitk > 1) {
+    long long total4 = (long long)p.M * p.N / 4;
+    hipLaunchKernelGGL(igemm_finalize_kernel, dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s, p);
+  }
+}
+
 template <int BN> void launch_bn(const IgemmParams& p, hipStream_t s) {
+  static const int v64 = getenv("SDSTREAM_IGEMM64") ? atoi(getenv("SDSTREAM_IGEMM64")) : 1;
+  static const int x8_below = getenv("SDSTREAM_X8_BELOW") ? atoi(getenv("SDSTREAM_X8_BELOW")) : 400;
+  if (v64 && p.C1 % 64 == 0 && p.C2 % 64 == 0) {
+    const int blocks = ((p.M + 127) / 128) * ((p.N + BN - 1) / BN) * (p.splitk > 1 ? p.splitk : 1);
+    static const int bm64 = getenv("SDSTREAM_BM64_BELOW") ? atoi(getenv("SDSTREAM_BM64_BELOW")) : 0;
+    if (blocks < bm64) launch_cfg64<64, BN>(p, s);
+    else if (blocks < x8_below) launch_cfg64x8<128, BN>(p, s);
+    else launch_cfg64<128, BN>(p, s);
+    return;
+  }
   static const int nsets = getenv("SDSTREAM_NSETS") ? atoi(getenv("SDSTREAM_NSETS")) : 3;
   static const int bm64_below = getenv("SDSTREAM_BM64_BELOW") ? atoi(getenv("SDSTREAM_BM64_BELOW")) : 0;
   const int tiles128 = ((p.M + 127) / 128) * ((p.N + BN - 1) / BN) * (p.splitk > 1 ? p.splitk : 1);

@@ -1,0 +1,53 @@
+"""Writes the oracle's expected outputs for the full-size (SD-shaped) workloads into tests/golden/*.npz.
+
+Calls only oracle/ and the seeded generators in workloads/ (never the HIP library).  The SD-shaped U-Net
+costs the float64 oracle ~10 s per row on 8 cores, so these prefixes are computed once here and the GPU
+tests compare against the stored arrays:
+  config 2: first 2 frames;  config 3: first 6 frames (3 valid outputs);  config 4: first 6 frames in each of
+  the three guidance modes;  config 5: first 5 frames of stream 0 (2 valid outputs);  plus one raw eps row
+  (t = 999) per U-Net shape.
+Usage: python tests/golden/make_golden.py [config ...]
+"""
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, os.path.dirname(os.path.dirname(HERE)))
+
+from oracle import stream as S  # noqa: E402
+from oracle import unet as U  # noqa: E402
+from workloads import CONFIGS, make_weights, stream_inputs  # noqa: E402
+
+FRAMES = {2: 2, 3: 6, 4: 6, 5: 5}
+
+
+def run(c: int):
+    wl = CONFIGS[c]
+    shape = U.UNetShape.from_dict(wl["unet"])
+    t0 = time.time()
+    net = U.UNet(shape, make_weights(U.manifest(shape), wl["seeds"]["weights"], wl["init"], wl["dtype"] == "bf16"))
+    frames = FRAMES[c]
+    inp = stream_inputs(wl, frames)
+    ctx, neg = torch.as_tensor(inp["context"]), torch.as_tensor(inp["neg_context"])
+    ts = list(wl["timesteps"])
+    modes = wl["cfg_mode"] if isinstance(wl["cfg_mode"], tuple) else (wl["cfg_mode"],)
+    out = {"frames": np.int64(frames)}
+    eps = net(torch.as_tensor(inp["x0"][0][:1]), [ts[0]], ctx)
+    out["eps_row0"] = eps.numpy().astype(np.float32)
+    for mode in modes:
+        sb = S.StreamBatch(net, ts, inp["noise"][:, :1], mode, wl["gamma"], wl["delta"])
+        for k in range(frames):
+            o, valid = sb.step(inp["x0"][k][:1], ctx, neg)
+            out[f"mode{mode}_frame{k}"] = o.numpy().astype(np.float32)
+            out[f"mode{mode}_valid{k}"] = np.bool_(valid)
+            print(f"config {c} mode {mode} frame {k} valid={valid} ({time.time() - t0:.0f} s)", flush=True)
+    np.savez_compressed(os.path.join(HERE, f"config{c}.npz"), **out)
+
+
+if __name__ == "__main__":
+    for c in ([int(a) for a in sys.argv[1:]] or [2, 3, 4, 5]):
+        run(c)

@@ -1,0 +1,157 @@
+"""GPU parity at the full workload sizes (SD-shaped U-Net, bf16), in the launch configuration bench.py times.
+
+The float64 oracle needs ~10 s per U-Net row at this size, so its outputs for a prefix of each stream are
+stored in tests/golden/config*.npz (written by tests/golden/make_golden.py, which calls only oracle/).  Beyond the
+prefix the Stream Batch == sequential-denoising property (Sec. 3.1) is checked on sampled frames, with the
+sequential side built from single-row calls of the U-Net entry point and float64 scheduler arithmetic.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from workloads import CONFIGS, ssf_frames, stream_inputs
+
+from util import cuda, gpu_engine, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-2      # ||g-o|| / ||o|| on every valid output latent (and on raw eps)
+TOL_SEQ = 2e-2       # stream vs sequential, both on the GPU in bf16 (different batch => different tiling / split-K)
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def _golden(c):
+    path = os.path.join(HERE, "golden", f"config{c}.npz")
+    if not os.path.exists(path):
+        pytest.skip(f"{path} missing: run tests/golden/make_golden.py {c}")
+    return np.load(path)
+
+
+def _schedule(ts):
+    betas = np.linspace(0.00085 ** 0.5, 0.012 ** 0.5, 1000, dtype=np.float64) ** 2
+    al = np.cumprod(1.0 - betas)[list(ts)]
+    return np.sqrt(al), np.sqrt(1.0 - al)
+
+
+def _sequential_on_gpu(eng, x0, ts, noise, ctx, neg, mode, gamma, delta):
+    """n single-row U-Net calls one after the other for ONE frame; x0, noise[i]: numpy [C,H,W]."""
+    a, b = _schedule(ts)
+    eps = torch.empty(1, *x0.shape, device="cuda")
+
+    def unet(x, t, c):
+        eng.unet_forward(cuda(x[None].astype(np.float32)), [t], c, eps)
+        torch.cuda.synchronize()
+        return eps[0].cpu().numpy().astype(np.float64)
+
+    x = a[0] * x0.astype(np.float64) + b[0] * noise[0]
+    ref = None
+    for i, t in enumerate(ts):
+        e = unet(x, t, ctx)
+        if mode == 1:
+            en = unet(x, t, neg)
+            g = en + gamma * (e - en)
+        elif mode in (2, 3):
+            if i == 0:
+                ref = x0.astype(np.float64) if mode == 2 else (x - b[0] * unet(x, t, neg)) / a[0]
+            v = (x - a[i] * ref) / b[i]
+            g = delta * v + gamma * (e - delta * v)
+        else:
+            g = e
+        x0_hat = (x - b[i] * g) / a[i]
+        if i + 1 < len(ts):
+            x = a[i + 1] * x0_hat + b[i + 1] * noise[i + 1]
+    return x0_hat
+
+
+def _run_stream(c, mode, frames, check_seq=()):
+    wl = CONFIGS[c]
+    gold = _golden(c)
+    ts = list(wl["timesteps"])
+    n, S = len(ts), wl["n_streams"]
+    inp = stream_inputs(wl, frames)
+    eng = gpu_engine(wl, "bf16", cfg_mode=mode)
+    eng.set_noise(inp["noise"])
+    ctx, neg = cuda(inp["context"]), cuda(inp["neg_context"])
+    out = torch.empty(S, *inp["x0"].shape[2:], device="cuda")
+    errs, outs = [], {}
+    for k in range(frames):
+        valid = eng.step(cuda(inp["x0"][k]), ctx, neg, 1, ts, wl["gamma"], wl["delta"], out)
+        torch.cuda.synchronize()
+        assert valid == (k >= n - 1)
+        got = out.cpu().numpy()
+        assert np.isfinite(got).all()
+        outs[k] = got
+        if k < int(gold["frames"]) and valid:
+            assert bool(gold[f"mode{mode}_valid{k}"])
+            errs.append(rel_l2(got[:1], gold[f"mode{mode}_frame{k}"]))
+    assert len(errs) == int(gold["frames"]) - (n - 1)
+    seq_errs = []
+    for (f, s) in check_seq:          # frame f of stream s leaves the queue at call f + n - 1
+        want = _sequential_on_gpu(eng, inp["x0"][f, s], ts, inp["noise"][:, s], ctx, neg, mode, wl["gamma"], wl["delta"])
+        seq_errs.append(rel_l2(outs[f + n - 1][s], want))
+    eng.close()
+    return errs, seq_errs
+
+
+def test_config2_single_step_sd21_shape():
+    wl = CONFIGS[2]
+    gold = _golden(2)
+    inp = stream_inputs(wl, 2)
+    eng = gpu_engine(wl, "bf16", cfg_mode=0)
+    eps = torch.empty(1, 4, 64, 64, device="cuda")
+    eng.unet_forward(cuda(inp["x0"][0][:1]), [999], cuda(inp["context"]), eps)
+    torch.cuda.synchronize()
+    assert rel_l2(eps.cpu().numpy(), gold["eps_row0"]) <= TOL_BF16
+    eng.close()
+    errs, _ = _run_stream(2, 0, 2)
+    assert max(errs) <= TOL_BF16
+
+
+def test_config3_stream_batch_of_four():
+    wl = CONFIGS[3]
+    gold = _golden(3)
+    inp = stream_inputs(wl, 1)
+    eng = gpu_engine(wl, "bf16", cfg_mode=0)
+    eps = torch.empty(1, 4, 64, 64, device="cuda")
+    eng.unet_forward(cuda(inp["x0"][0][:1]), [999], cuda(inp["context"]), eps)
+    torch.cuda.synchronize()
+    assert rel_l2(eps.cpu().numpy(), gold["eps_row0"]) <= TOL_BF16
+    eng.close()
+    errs, seq = _run_stream(3, 0, 40, check_seq=[(2, 0), (33, 0)])
+    assert max(errs) <= TOL_BF16
+    assert max(seq) <= TOL_SEQ
+
+
+@pytest.mark.parametrize("mode", [1, 2, 3])
+def test_config4_guidance_modes(mode):
+    errs, seq = _run_stream(4, mode, 8, check_seq=[(3, 0)])
+    assert max(errs) <= TOL_BF16
+    assert max(seq) <= TOL_SEQ
+
+
+def test_config5_four_streams_768():
+    wl = CONFIGS[5]
+    errs, seq = _run_stream(5, wl["cfg_mode"], 6, check_seq=[(1, 1), (2, 3)])
+    assert max(errs) <= TOL_BF16
+    assert max(seq) <= TOL_SEQ
+
+
+def test_config5_ssf_sequence_bit_exact():
+    from oracle import ssf as F
+    import paper_2312_12491_amd as sd
+    wl = CONFIGS[1]
+    spec = CONFIGS[5]["ssf"]
+    eng = sd.Engine(sd.config_from_dict(wl["unet"], wl["latent"], "fp32", 1, 1, 0))
+    flt = F.Filter(spec["eta"], spec["draw_seed"])
+    skips, band = 0, 0
+    for k, f in enumerate(ssf_frames(spec["frame_seed"], spec["frames"], spec["h"], spec["w"])):
+        want_skip, want_p = flt(f, k)
+        skip, p = eng.ssf(cuda(f), spec["h"], spec["w"], spec["eta"], spec["draw_seed"], k)
+        assert skip == want_skip, k
+        assert p == want_p or abs(p - want_p) <= 2.3e-16 * max(p, want_p), k
+        skips += skip
+        band += 0.0 < p < 1.0
+    assert 0 < skips < spec["frames"] and band > 0
+    eng.close()
