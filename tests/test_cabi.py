@@ -1,0 +1,59 @@
+"""CPU-side checks of the C ABI: the built library exports every function the header declares, and the host half
+of the similarity filter agrees with the oracle (no GPU call is made here)."""
+import ctypes
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "sdstream.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sdstream_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2312_12491_amd import binding
+    names = _declared()
+    assert len(names) >= 20
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(binding.exported_symbols()) == names      # the Python binding wraps all of them, and nothing else
+
+
+def test_create_rejects_bad_arguments_without_a_gpu_call():
+    from paper_2312_12491_amd import binding
+    l = binding.lib()
+    assert l.sdstream_create(None, None) == -1
+    assert b"null" in l.sdstream_last_error(None)
+    from workloads import CONFIGS
+    cfg = binding.config_from_dict(dict(CONFIGS[1]["unet"], head_dim=0), (8, 8), "fp32", 2, 1, 0)   # no head field set
+    h = ctypes.c_void_p()
+    assert l.sdstream_create(ctypes.byref(cfg), ctypes.byref(h)) == -1 and not h.value
+    cfg = binding.config_from_dict(CONFIGS[1]["unet"], (9, 8), "fp32", 2, 1, 0)                    # 9 not divisible by 2
+    assert l.sdstream_create(ctypes.byref(cfg), ctypes.byref(h)) == -1 and not h.value
+    assert l.sdstream_step(None, None, None, None, 0, None, 1.0, 1.0, None, None, None) == -1
+
+
+def test_ssf_decide_matches_the_oracle():
+    from oracle import ssf as F
+    from paper_2312_12491_amd import ssf_decide
+    rng = np.random.default_rng(0)
+    for k in range(2000):
+        a = rng.integers(0, 256, 300, dtype=np.uint8)
+        b = np.clip(a.astype(np.int64) + rng.integers(-12, 13, 300), 0, 255).astype(np.uint8) if k % 3 else a
+        d, nt, nr = F.sums(a, b)
+        eta = [0.9, 0.98, 1.0][k % 3]
+        skip, p = ssf_decide(d, nt, nr, eta, 7000, k)
+        want_p = F.skip_probability(F.cosine(d, nt, nr), eta)
+        assert p == want_p
+        assert skip == (F.uniform(7000, k) < want_p)
+    assert ssf_decide(0, 0, 5, 0.5, 1, 1) == (False, 0.0)
+    assert ssf_decide(25, 25, 25, 0.98, 1, 1)[1] == 1.0
+    assert ssf_decide(25, 25, 25, 1.0, 1, 1) == (False, 0.0)
