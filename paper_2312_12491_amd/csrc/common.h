@@ -33,8 +33,9 @@ struct IgemmParams {
   const void* residual;  // [M][Nout] or null
   void* out;             // [M][Nout], Nout = N (N/2 for GEGLU)
   int epilogue;
-  int splitk;            // MFMA kernel only: number of K splits, fp32 partials [splitk][M][N] in `workspace`
-  float* workspace;
+  int splitk;            // set by the MFMA launcher: number of K splits, fp32 partials [splitk][M][N] in `workspace`
+  float* workspace;      // MFMA kernel only: split-K scratch (null forbids split-K)
+  long long workspace_floats;
   const void* zeros;     // MFMA kernel only: >= 16 readable zero bytes (source of padded / out-of-range rows)
 };
 

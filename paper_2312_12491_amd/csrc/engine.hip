@@ -747,20 +747,8 @@ void launch_op(sdstream* h, const Op& op0, int N, const int* kv_select, hipStrea
       g.M = N * op0.rows_per_sample;
       g.zeros = h->persist + h->off_zeros;
       if (op0.mfma) {
-        // few output tiles: split K across blocks so the whole chip streams the weights
-        const int bn = g.N % 160 == 0 ? 160 : (g.N % 128 == 0 ? 128 : 64);
-        const int tiles = ((g.M + 127) / 128) * ((g.N + bn - 1) / bn);
-        const int stages = g.K / 64;
-        if (g.epilogue == EPI_NONE && tiles <= 128 && stages >= 8) {
-          int sk = 512 / tiles;
-          if (sk > stages / 4) sk = stages / 4;
-          const size_t mn = (size_t)g.M * g.N;
-          if ((size_t)sk * mn > kSplitKWorkspaceFloats) sk = (int)(kSplitKWorkspaceFloats / mn);
-          if (sk > 1) {
-            g.splitk = sk;
-            g.workspace = (float*)(h->persist + h->off_splitk);
-          }
-        }
+        g.workspace = (float*)(h->persist + h->off_splitk);
+        g.workspace_floats = (long long)kSplitKWorkspaceFloats;
         launch_igemm_mfma(g, s);
       }
       else if (bf) launch_igemm_generic<bf16_t>(g, s);

@@ -13,6 +13,7 @@
 // turns into the output.
 #include "common.h"
 
+#include <stdio.h>
 #include <stdlib.h>
 
 namespace {
@@ -331,21 +332,13 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma64_kernel(IgemmParams p, int
       iy = min(max(iy, 0), Hs - 1) >> ups;
       ix = min(max(ix, 0), Wsz - 1) >> ups;
       unsigned off = ((ld_pix0[i] + (unsigned)(iy * p.Win + ix)) * (unsigned)Cs + (unsigned)(c + cq * 8)) * 2u;
-#ifdef IGEMM_NO_GLOBAL
-      areg[set][i] = u32x4{off, off, off, off};
-#else
       areg[set][i] = *(const u32x4*)(src + off);
-#endif
       m |= (ok ? 1u : 0u) << i;
     }
     okm[set] = m;
     const unsigned kb = (unsigned)min(l_stage, stage_last) * 2048u;
 #pragma unroll
-#ifdef IGEMM_NO_GLOBAL
-    for (int i = 0; i < NLB; ++i) breg[set][i] = u32x4{kb, kb, kb, boff[i]};
-#else
     for (int i = 0; i < NLB; ++i) breg[set][i] = *(const u32x4*)(Wp + (boff[i] + kb));
-#endif
     ++l_stage;
     l_c += 64;
     if (l_c >= Ct) {
@@ -369,47 +362,25 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma64_kernel(IgemmParams p, int
     for (int i = 0; i < NLA; ++i) {
       u32x4 v = areg[set][i];
       if (!((okm[set] >> i) & 1u)) v = u32x4{0u, 0u, 0u, 0u};
-#ifndef IGEMM_NO_LDSWRITE
       *(u32x4*)(sa + ld_lds[i]) = v;
-#else
-      if (v[0] == 0x12345u) *(u32x4*)(sa + ld_lds[i]) = v;
-#endif
     }
 #pragma unroll
-    for (int i = 0; i < NLB; ++i) {
-#ifndef IGEMM_NO_LDSWRITE
-      *(u32x4*)(sb + (tid + i * 256) * 16) = breg[set][i];
-#else
-      if (breg[set][i][0] == 0x12345u) *(u32x4*)(sb + (tid + i * 256) * 16) = breg[set][i];
-#endif
-    }
-#ifndef IGEMM_NO_BARRIER
+    for (int i = 0; i < NLB; ++i) *(u32x4*)(sb + (tid + i * 256) * 16) = breg[set][i];
     __syncthreads();
-#endif
     load(IC<set ^ 1>{});
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
       bf16x8 af[MT], bfr[NT];
 #pragma unroll
-#ifdef IGEMM_NO_LDSREAD
-      for (int mt = 0; mt < MT; ++mt) for (int e = 0; e < 8; ++e) af[mt][e] = (bf16_t)(float)(lane + mt + buf);
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) for (int e = 0; e < 8; ++e) bfr[nt][e] = (bf16_t)(float)(lane + nt + buf);
-#else
       for (int mt = 0; mt < MT; ++mt)
         af[mt] = *(const bf16x8*)(sa + (wm * WTM + mt * 16 + (lane & 15)) * ROWB + ks * 64 + (lane >> 4) * 16);
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) bfr[nt] = *(const bf16x8*)(sb + ((wn * NT + nt) * 2 + ks) * 1024 + lane * 16);
-#endif
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
-#ifdef IGEMM_NO_MFMA
-          acc[mt][nt][0] += (float)bfr[nt][0] * (float)af[mt][0];
-#else
           acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[nt], af[mt], acc[mt][nt], 0, 0, 0);
-#endif
     }
     buf ^= 1;
   };
@@ -673,24 +644,60 @@ template <int BM, int BN> void launch_cfg64x8(const IgemmParams& p, hipStream_t 
   }
 }
 
-template <int BN> void launch_bn(const IgemmParams& p, hipStream_t s) {
-  static const int v64 = getenv("SDSTREAM_IGEMM64") ? atoi(getenv("SDSTREAM_IGEMM64")) : 1;
-  static const int x8_below = getenv("SDSTREAM_X8_BELOW") ? atoi(getenv("SDSTREAM_X8_BELOW")) : 400;
-  if (v64 && p.C1 % 64 == 0 && p.C2 % 64 == 0) {
-    const int blocks = ((p.M + 127) / 128) * ((p.N + BN - 1) / BN) * (p.splitk > 1 ? p.splitk : 1);
-    static const int bm64 = getenv("SDSTREAM_BM64_BELOW") ? atoi(getenv("SDSTREAM_BM64_BELOW")) : 0;
-    if (blocks < bm64) launch_cfg64<64, BN>(p, s);
-    else if (blocks < x8_below) launch_cfg64x8<128, BN>(p, s);
-    else launch_cfg64<128, BN>(p, s);
-    return;
-  }
-  static const int nsets = getenv("SDSTREAM_NSETS") ? atoi(getenv("SDSTREAM_NSETS")) : 3;
-  static const int bm64_below = getenv("SDSTREAM_BM64_BELOW") ? atoi(getenv("SDSTREAM_BM64_BELOW")) : 0;
-  const int tiles128 = ((p.M + 127) / 128) * ((p.N + BN - 1) / BN) * (p.splitk > 1 ? p.splitk : 1);
-  if (tiles128 < bm64_below) {
-    if (nsets == 4) launch_cfg<64, BN, 4>(p, s); else launch_cfg<64, BN, 3>(p, s);
+struct Choice { int variant, bn, splitk; };  // variant 0: 4 waves 128xBN, 1: 8 waves 128xBN, 2: 4 waves 64xBN, 3: 32-deep stages
+
+// Tile / kernel / split-K selection.  Rules of thumb from sweeps on MI355X: a grid that leaves compute units with one
+// 4-wave block is better served by the 8-wave kernel or by 64-row tiles; grids far below the chip size split K.
+Choice choose(const IgemmParams& p) {
+  Choice c;
+  const bool k64 = p.C1 % 64 == 0 && p.C2 % 64 == 0;
+  if (p.epilogue == EPI_GEGLU) c.bn = 128;
+  else if (p.N % 160 == 0) c.bn = 160;
+  else if (p.N % 128 == 0) c.bn = 128;
+  else c.bn = 64;
+  c.splitk = 1;
+  if (!k64) { c.variant = 3; return c; }
+  const int stages = p.K / 64;
+  const bool may_split = p.epilogue == EPI_NONE && p.workspace != nullptr;
+  const long long mn = (long long)p.M * p.N;
+  auto blocks = [&](int bm, int bn) { return ((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn); };
+  int sk = 1;
+  if (stages <= 30) {
+    // short K (the 1x1 layers): shrink the tile rather than split K
+    c.variant = 2;
+    if (blocks(64, c.bn) < 512 && p.N % 64 == 0) c.bn = 64;
+    const int nb = blocks(64, c.bn);
+    if (nb < 256 && stages >= 16) sk = 512 / nb < stages / 8 ? 512 / nb : stages / 8;
   } else {
-    if (nsets == 4) launch_cfg<128, BN, 4>(p, s); else launch_cfg<128, BN, 3>(p, s);
+    const int nb = blocks(128, c.bn);
+    if (nb < 400) sk = (512 + nb / 2) / nb < stages / 8 ? (512 + nb / 2) / nb : stages / 8;
+    if (!may_split) sk = 1;
+    if ((long long)sk * mn > p.workspace_floats) sk = (int)(p.workspace_floats / mn);
+    if (sk < 1) sk = 1;
+    c.variant = nb * sk >= 400 ? 0 : 1;
+  }
+  if (!may_split) sk = 1;
+  if ((long long)sk * mn > p.workspace_floats) sk = (int)(p.workspace_floats / mn);
+  c.splitk = sk > 1 ? sk : 1;
+  if (const char* t = getenv("SDSTREAM_TUNE")) {  // "variant,bn,splitk" for sweeps; unsupported combinations are ignored
+    int v = -1, bn = 0, sk = 0;
+    if (sscanf(t, "%d,%d,%d", &v, &bn, &sk) == 3) {
+      if (v >= 0 && v <= 3 && (k64 || v == 3)) c.variant = v;
+      if ((bn == 160 || bn == 128 || bn == 64) && !(p.epilogue == EPI_GEGLU && bn == 160)) c.bn = bn;
+      if (sk >= 1 && p.epilogue == EPI_NONE && p.workspace && (long long)sk * p.M * p.N <= p.workspace_floats &&
+          sk <= (c.variant == 3 ? p.K / 32 : p.K / 64))
+        c.splitk = sk;
+    }
+  }
+  return c;
+}
+
+template <int BN> void launch_bn(const IgemmParams& p, int variant, hipStream_t s) {
+  switch (variant) {
+    case 0: launch_cfg64<128, BN>(p, s); break;
+    case 1: launch_cfg64x8<128, BN>(p, s); break;
+    case 2: launch_cfg64<64, BN>(p, s); break;
+    default: launch_cfg<128, BN, 3>(p, s); break;
   }
 }
 
@@ -702,7 +709,6 @@ bool igemm_mfma_supported(const IgemmParams& p) {
   if (p.C1 % 32 || p.C2 % 32 || p.N % 16) return false;
   if (p.epilogue == EPI_GEGLU && p.N % 128) return false;
   if (p.epilogue == EPI_SILU) return false;
-  if (p.splitk > 1 && p.epilogue != EPI_NONE) return false;
   // the kernel addresses activations and weights with 32-bit byte offsets
   const long long samples = (p.M + (long long)p.Hout * p.Wout - 1) / ((long long)p.Hout * p.Wout);
   const long long cmax = p.C1 > p.C2 ? p.C1 : p.C2;
@@ -711,9 +717,11 @@ bool igemm_mfma_supported(const IgemmParams& p) {
   return true;
 }
 
-void launch_igemm_mfma(const IgemmParams& p, hipStream_t s) {
-  if (p.epilogue == EPI_GEGLU) launch_bn<128>(p, s);
-  else if (p.N % 160 == 0) launch_bn<160>(p, s);
-  else if (p.N % 128 == 0) launch_bn<128>(p, s);
-  else launch_bn<64>(p, s);
+void launch_igemm_mfma(const IgemmParams& p0, hipStream_t s) {
+  IgemmParams p = p0;
+  const Choice c = choose(p);
+  p.splitk = c.splitk;
+  if (c.bn == 160) launch_bn<160>(p, c.variant, s);
+  else if (c.bn == 128) launch_bn<128>(p, c.variant, s);
+  else launch_bn<64>(p, c.variant, s);
 }
