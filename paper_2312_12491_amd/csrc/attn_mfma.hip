@@ -1,12 +1,15 @@
 // bf16 flash attention on the gfx950 matrix cores (v_mfma_f32_16x16x32_bf16), online softmax in fp32.
 //
-// One 256-thread block = 128 queries of one (sample, head); each wave owns 2 tiles of 16 queries.  K/V tiles
-// of 64 keys are staged in LDS (K as [key][d], V transposed as [d][key]) and shared by the four waves.
+// One 256-thread block = 64*QT queries of one (sample, head); each wave owns QT tiles of 16 queries.  K/V tiles
+// of 64 keys are staged in double-buffered LDS (K as [key][d], V transposed as [d][key]) and shared by the waves;
+// every K / V fragment read from LDS is used for all QT query tiles of the wave.
 // Scores are computed transposed, S^T = K Q^T, so a lane holds 16 keys of ONE query per tile: the running
 // max / sum / rescale factor are per-lane scalars and the probabilities feed the second MFMA (O^T = V^T P^T)
 // straight from registers.  The contraction order of that MFMA is a fixed permutation of the keys, applied
 // identically to P (register order) and to the V^T fragment read.
 #include "common.h"
+
+#include <stdlib.h>
 
 namespace {
 
@@ -14,17 +17,33 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-constexpr int QT = 2;     // query tiles (of 16) per wave
-constexpr int BQ = 4 * QT * 16;
 constexpr int BKV = 64;
 
-template <int DK, int DT>  // DK = ceil(d/32) contraction steps of Q K^T; DT = ceil(d/16) output tiles of P V
-__global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p) {
+// Reductions over the four lanes {li, li+16, li+32, li+48} that share a query, on the vector ALU:
+// v_permlane16_swap / v_permlane32_swap with both operands equal leave (x[l], x[l^16]) resp. (x[l], x[l^32]) in a lane.
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float quad_max(float x) {
+  u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float quad_sum(float x) {
+  u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// DK = ceil(d/32) contraction steps of Q K^T; DT = ceil(d/16) output tiles of P V; QT = query tiles (of 16) per wave
+template <int DK, int DT, int QT>
+__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
+  constexpr int BQ = 4 * QT * 16;
   constexpr int KPITCH = DK * 64 + 16;   // bytes per key row of the K tile
   constexpr int VPITCH = BKV * 2 + 16;   // bytes per d row of the V^T tile
   constexpr int DPAD = DT * 16;
-  __shared__ __attribute__((aligned(16))) unsigned char Ks[BKV * KPITCH];
-  __shared__ __attribute__((aligned(16))) unsigned char Vs[DPAD * VPITCH];
+  constexpr int KBYTES = BKV * KPITCH, VBYTES = DPAD * VPITCH, TILE = KBYTES + VBYTES;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // two [K | V^T] tiles
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 4, li = lane & 15;
@@ -38,9 +57,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p) {
                                       : (long long)sample * p.kv_sample_stride;
   const int q0 = blockIdx.x * BQ + wave * (QT * 16);
 
-  // zero both tiles once: padding columns / rows are never written again
-  for (int i = tid; i < (BKV * KPITCH) / 16; i += 256) ((uint4*)Ks)[i] = make_uint4(0, 0, 0, 0);
-  for (int i = tid; i < (DPAD * VPITCH) / 16; i += 256) ((uint4*)Vs)[i] = make_uint4(0, 0, 0, 0);
+  // zero both buffers once: padding columns / rows are never written again
+  for (int i = tid; i < (2 * TILE) / 16; i += 256) ((uint4*)smem)[i] = make_uint4(0, 0, 0, 0);
 
   // Q fragments (B operand: column = query li, 8 consecutive d)
   bf16x8 qf[QT][DK];
@@ -90,7 +108,9 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p) {
       vreg[i] = v;
     }
   };
-  auto store_tiles = [&]() {
+  auto store_tiles = [&](int b) {
+    unsigned char* Ks = smem + b * TILE;
+    unsigned char* Vs = Ks + KBYTES;
 #pragma unroll
     for (int i = 0; i < KSLOTS; ++i) {
       int ch = tid + i * 256;
@@ -111,67 +131,86 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p) {
   };
 
   load_tiles(0);
-  for (int j0 = 0; j0 < p.Skv; j0 += BKV) {
-    __syncthreads();  // previous tile fully consumed (also orders the initial zero fill)
-    store_tiles();
-    __syncthreads();
-    if (j0 + BKV < p.Skv) load_tiles(j0 + BKV);
+  __syncthreads();  // zero fill done
+  store_tiles(0);
+  __syncthreads();
+  int buf = 0;
+  for (int j0 = 0; j0 < p.Skv; j0 += BKV, buf ^= 1) {
+    const unsigned char* Ks = smem + buf * TILE;
+    const unsigned char* Vs = Ks + KBYTES;
+    const bool more = j0 + BKV < p.Skv;
+    if (more) load_tiles(j0 + BKV);  // in flight while this tile is multiplied
 
+    // S^T tiles: rows = keys 16*kt + 4g + v, column = query li; every K fragment serves all QT query tiles
+    f32x4 sacc[QT][4];
 #pragma unroll
-    for (int t = 0; t < QT; ++t) {
-      // S^T tiles: rows = keys 16*kt + 4g + v, column = query li
-      f32x4 s[4];
+    for (int kt = 0; kt < 4; ++kt) {
 #pragma unroll
-      for (int kt = 0; kt < 4; ++kt) {
-        s[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int t = 0; t < QT; ++t) sacc[t][kt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int ks = 0; ks < DK; ++ks) {
-          bf16x8 kf = *(const bf16x8*)(Ks + (kt * 16 + li) * KPITCH + (ks * 32 + g * 8) * 2);
-          s[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[t][ks], s[kt], 0, 0, 0);
-        }
-      }
-      float mx = -1e30f;
+      for (int ks = 0; ks < DK; ++ks) {
+        bf16x8 kf = *(const bf16x8*)(Ks + (kt * 16 + li) * KPITCH + (ks * 32 + g * 8) * 2);
 #pragma unroll
-      for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          float x = (j0 + kt * 16 + g * 4 + v < p.Skv) ? s[kt][v] * sc : -1e30f;
-          s[kt][v] = x;
-          mx = fmaxf(mx, x);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float mnew = fmaxf(mrun[t], mx);
-      const float alpha = __builtin_amdgcn_exp2f(mrun[t] - mnew);
-      mrun[t] = mnew;
-      float sum = 0.f;
-      bf16x8 pf[2];
-#pragma unroll
-      for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          float e = __builtin_amdgcn_exp2f(s[kt][v] - mnew);
-          sum += e;
-          pf[kt >> 1][(kt & 1) * 4 + v] = (bf16_t)e;
-        }
-      sum += __shfl_xor(sum, 16);
-      sum += __shfl_xor(sum, 32);
-      lrun[t] = lrun[t] * alpha + sum;
-      // O^T += V^T P^T : rows = d (16*dt + 4g + v), column = query li
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-        f32x4 acc = o[t][dt] * alpha;
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-          const unsigned char* row = Vs + (dt * 16 + li) * VPITCH + (kk * 32 + g * 4) * 2;
-          bf16x4 lo = *(const bf16x4*)row;
-          bf16x4 hi = *(const bf16x4*)(row + 32);
-          bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[kk], acc, 0, 0, 0);
-        }
-        o[t][dt] = acc;
+        for (int t = 0; t < QT; ++t)
+          sacc[t][kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[t][ks], sacc[t][kt], 0, 0, 0);
       }
     }
+    bf16x8 pf[QT][2];
+    float alpha[QT];
+    bool rescale = false;
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+      f32x4(&s)[4] = sacc[t];
+      if (j0 + BKV > p.Skv) {  // ragged last tile: keys past the end must not win the max or add to the sum
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            if (j0 + kt * 16 + g * 4 + v >= p.Skv) s[kt][v] = -3.0e38f;
+      }
+      float mx = s[0][0];
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) mx = fmaxf(mx, s[kt][v]);
+      mx = quad_max(mx);
+      const float mnew = fmaxf(mrun[t], mx * sc);   // running max of the scaled scores (base-2 exponent units)
+      alpha[t] = __builtin_amdgcn_exp2f(mrun[t] - mnew);
+      mrun[t] = mnew;
+      float sum = 0.f;
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          float e = __builtin_amdgcn_exp2f(fmaf(s[kt][v], sc, -mnew));
+          sum += e;
+          pf[t][kt >> 1][(kt & 1) * 4 + v] = (bf16_t)e;
+        }
+      sum = quad_sum(sum);
+      lrun[t] = lrun[t] * alpha[t] + sum;
+      rescale = rescale || __any(alpha[t] != 1.0f);
+    }
+    // O^T += V^T P^T : rows = d (16*dt + 4g + v), column = query li.  The old sums are rescaled only when some
+    // query of the wave moved its running max (wave-uniform test); every V fragment serves all QT query tiles.
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      if (rescale) {
+#pragma unroll
+        for (int t = 0; t < QT; ++t) o[t][dt] *= alpha[t];
+      }
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+        const unsigned char* row = Vs + (dt * 16 + li) * VPITCH + (kk * 32 + g * 4) * 2;
+        bf16x4 lo = *(const bf16x4*)row;
+        bf16x4 hi = *(const bf16x4*)(row + 32);
+        bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+        for (int t = 0; t < QT; ++t) o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[t][kk], o[t][dt], 0, 0, 0);
+      }
+    }
+    // the other buffer was last read one iteration ago, before the barrier every wave has passed since
+    if (more) store_tiles(buf ^ 1);
+    __syncthreads();
   }
 
   bf16_t* O = (bf16_t*)p.out;
@@ -192,9 +231,28 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnParams p) {
   }
 }
 
-template <int DK, int DT> void launch_cfg(const AttnParams& p, hipStream_t s) {
+template <int DK, int DT, int QT> void launch_qt(const AttnParams& p, hipStream_t s) {
+  constexpr int BQ = 4 * QT * 16;
+  constexpr int LDS = 2 * (BKV * (DK * 64 + 16) + DT * 16 * (BKV * 2 + 16));
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipFuncSetAttribute((const void*)attn_mfma_kernel<DK, DT, QT>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    attr_set = true;
+  }
   dim3 grid((p.Sq + BQ - 1) / BQ, p.heads, p.samples);
-  hipLaunchKernelGGL((attn_mfma_kernel<DK, DT>), grid, dim3(256), 0, s, p);
+  hipLaunchKernelGGL((attn_mfma_kernel<DK, DT, QT>), grid, dim3(256), LDS, s, p);
+}
+
+// more query tiles per wave amortise the K / V fragment reads; fewer keep small problems spread over the chip
+template <int DK, int DT> void launch_cfg(const AttnParams& p, hipStream_t s) {
+  static const int force = getenv("SDSTREAM_ATTN_QT") ? atoi(getenv("SDSTREAM_ATTN_QT")) : 0;
+  auto blocks = [&](int qt) { return (long long)((p.Sq + 64 * qt - 1) / (64 * qt)) * p.heads * p.samples; };
+  int qt = 1;
+  if (blocks(2) >= 512) qt = 2;
+  if constexpr (DT <= 4) { if (blocks(4) >= 512) qt = 4; }
+  if (force) qt = force;
+  if constexpr (DT <= 4) { if (qt == 4) { launch_qt<DK, DT, 4>(p, s); return; } }
+  if (qt == 1) launch_qt<DK, DT, 1>(p, s); else launch_qt<DK, DT, 2>(p, s);
 }
 
 }  // namespace
