@@ -401,7 +401,9 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma64_kernel(IgemmParams p, int
 // stage between them (k 0..31 / k 32..63 of the same 128 x BN tile) and add their accumulators through
 // LDS at the end.  Tile, traffic and LDS layout are those of the 4-wave kernel.
 // ---------------------------------------------------------------------------------------------------
-template <int BM, int BN>
+// NSB = register sets for the weight stream (prefetch distance NSB-1 stages): 2 normally, 4 for the few-row layers
+// whose time is the HBM stream of their weights.
+template <int BM, int BN, int NSB>
 __global__ __launch_bounds__(512) void igemm_mfma64x8_kernel(IgemmParams p, int mtiles, int ksteps_total,
                                                              int stages_per_split) {
   constexpr int WM = 2, WN = 2;
@@ -459,7 +461,6 @@ __global__ __launch_bounds__(512) void igemm_mfma64x8_kernel(IgemmParams p, int 
   const int stage0 = blockIdx.z * stages_per_split;
   int nstages = total_stages - stage0;
   if (nstages > stages_per_split) nstages = stages_per_split;
-  int l_stage = stage0;
   const int stage_last = total_stages - 1;
   int l_c, l_ky, l_kx;
   {
@@ -470,9 +471,10 @@ __global__ __launch_bounds__(512) void igemm_mfma64x8_kernel(IgemmParams p, int 
     l_kx = tap - l_ky * p.ksize;
   }
 
-  u32x4 areg[2][NLA], breg[2][NLB];
+  u32x4 areg[2][NLA], breg[NSB][NLB];
   unsigned okm[2];
-  auto load = [&](auto setc) {
+  int lb_stage = stage0;
+  auto load_a = [&](auto setc) {
     constexpr int set = decltype(setc)::value;
     const char* src;
     int Cs, c = l_c;
@@ -489,15 +491,18 @@ __global__ __launch_bounds__(512) void igemm_mfma64x8_kernel(IgemmParams p, int 
       m |= (ok ? 1u : 0u) << i;
     }
     okm[set] = m;
-    const unsigned kb = (unsigned)min(l_stage, stage_last) * 2048u;
-#pragma unroll
-    for (int i = 0; i < NLB; ++i) breg[set][i] = *(const u32x4*)(Wp + (boff[i] + kb));
-    ++l_stage;
     l_c += 64;
     if (l_c >= Ct) {
       l_c = 0;
       if (++l_kx == p.ksize) { l_kx = 0; ++l_ky; }
     }
+  };
+  auto load_b = [&](auto setc) {
+    constexpr int set = decltype(setc)::value;
+    const unsigned kb = (unsigned)min(lb_stage, stage_last) * 2048u;
+#pragma unroll
+    for (int i = 0; i < NLB; ++i) breg[set][i] = *(const u32x4*)(Wp + (boff[i] + kb));
+    ++lb_stage;
   };
 
   f32x4 acc[MT][NT];
@@ -507,24 +512,26 @@ __global__ __launch_bounds__(512) void igemm_mfma64x8_kernel(IgemmParams p, int 
     for (int j = 0; j < NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   int buf = 0;
-  auto stage = [&](auto setc) {
-    constexpr int set = decltype(setc)::value;
+  auto stage = [&](auto uc) {
+    constexpr int u = decltype(uc)::value;   // stage index modulo 4
+    constexpr int sa_set = u & 1, sb_set = u % NSB;
     unsigned char* sa = lds + buf * STAGE;
     unsigned char* sb = sa + ABYTES;
 #pragma unroll
     for (int i = 0; i < NLA; ++i) {
-      u32x4 v = areg[set][i];
-      if (!((okm[set] >> i) & 1u)) v = u32x4{0u, 0u, 0u, 0u};
+      u32x4 v = areg[sa_set][i];
+      if (!((okm[sa_set] >> i) & 1u)) v = u32x4{0u, 0u, 0u, 0u};
       *(u32x4*)(sa + ld_lds[i]) = v;
     }
 #pragma unroll
     for (int i = 0; i < NLB; ++i) {
       int q = tid + i * 512;
       if (q >= NBCH) q = NBCH - 1;
-      *(u32x4*)(sb + q * 16) = breg[set][i];
+      *(u32x4*)(sb + q * 16) = breg[sb_set][i];
     }
     __syncthreads();
-    load(IC<set ^ 1>{});
+    load_a(IC<sa_set ^ 1>{});
+    load_b(IC<(u + NSB - 1) % NSB>{});
     bf16x8 af[MT], bfr[NT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -539,11 +546,17 @@ __global__ __launch_bounds__(512) void igemm_mfma64x8_kernel(IgemmParams p, int 
     buf ^= 1;
   };
 
-  load(IC<0>{});
-  for (int base = 0; base < nstages; base += 2) {
+  load_a(IC<0>{});
+  load_b(IC<0>{});
+  if constexpr (NSB > 2) { load_b(IC<1>{}); load_b(IC<2>{}); }
+  for (int base = 0; base < nstages; base += 4) {
     stage(IC<0>{});
     if (base + 1 >= nstages) break;
     stage(IC<1>{});
+    if (base + 2 >= nstages) break;
+    stage(IC<2>{});
+    if (base + 3 >= nstages) break;
+    stage(IC<3>{});
   }
 
   // fold the second wave group into the first through LDS, two m-tiles at a time
@@ -624,11 +637,11 @@ template <int BM, int BN> void launch_cfg64(const IgemmParams& p, hipStream_t s)
   }
 }
 
-template <int BM, int BN> void launch_cfg64x8(const IgemmParams& p, hipStream_t s) {
+template <int BM, int BN, int NSB> void launch_cfg64x8(const IgemmParams& p, hipStream_t s) {
   constexpr int LDS = 2 * (BM * 144 + BN * 128);
   static bool attr_set = false;
   if (!attr_set) {
-    hipFuncSetAttribute((const void*)igemm_mfma64x8_kernel<BM, BN>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    hipFuncSetAttribute((const void*)igemm_mfma64x8_kernel<BM, BN, NSB>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     attr_set = true;
   }
   const int mtiles = (p.M + BM - 1) / BM, ntiles = (p.N + BN - 1) / BN;
@@ -637,14 +650,15 @@ template <int BM, int BN> void launch_cfg64x8(const IgemmParams& p, hipStream_t 
   const int splitk = p.splitk > 1 ? p.splitk : 1;
   const int sps = (total_stages + splitk - 1) / splitk;
   dim3 grid(mtiles * ntiles, 1, splitk);
-  hipLaunchKernelGGL((igemm_mfma64x8_kernel<BM, BN>), grid, dim3(512), LDS, s, p, mtiles, ksteps_total, sps);
+  hipLaunchKernelGGL((igemm_mfma64x8_kernel<BM, BN, NSB>), grid, dim3(512), LDS, s, p, mtiles, ksteps_total, sps);
   if (splitk > 1) {
     long long total4 = (long long)p.M * p.N / 4;
     hipLaunchKernelGGL(igemm_finalize_kernel, dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s, p);
   }
 }
 
-struct Choice { int variant, bn, splitk; };  // variant 0: 4 waves 128xBN, 1: 8 waves 128xBN, 2: 4 waves 64xBN, 3: 32-deep stages
+struct Choice { int variant, bn, splitk; };  // variant 0: 4 waves 128xBN, 1: 8 waves 128xBN, 2: 4 waves 64xBN, 3: 32-deep
+                                             // stages, 4: 8 waves with a deep weight prefetch
 
 // Tile / kernel / split-K selection.  Rules of thumb from sweeps on MI355X: a grid that leaves compute units with one
 // 4-wave block is better served by the 8-wave kernel or by 64-row tiles; grids far below the chip size split K.
@@ -682,7 +696,7 @@ Choice choose(const IgemmParams& p) {
   if (const char* t = getenv("SDSTREAM_TUNE")) {  // "variant,bn,splitk" for sweeps; unsupported combinations are ignored
     int v = -1, bn = 0, sk = 0;
     if (sscanf(t, "%d,%d,%d", &v, &bn, &sk) == 3) {
-      if (v >= 0 && v <= 3 && (k64 || v == 3)) c.variant = v;
+      if (v >= 0 && v <= 4 && (k64 || v == 3)) c.variant = v;
       if ((bn == 160 || bn == 128 || bn == 64) && !(p.epilogue == EPI_GEGLU && bn == 160)) c.bn = bn;
       if (sk >= 1 && p.epilogue == EPI_NONE && p.workspace && (long long)sk * p.M * p.N <= p.workspace_floats &&
           sk <= (c.variant == 3 ? p.K / 32 : p.K / 64))
@@ -695,7 +709,8 @@ Choice choose(const IgemmParams& p) {
 template <int BN> void launch_bn(const IgemmParams& p, int variant, hipStream_t s) {
   switch (variant) {
     case 0: launch_cfg64<128, BN>(p, s); break;
-    case 1: launch_cfg64x8<128, BN>(p, s); break;
+    case 1: launch_cfg64x8<128, BN, 2>(p, s); break;
+    case 4: launch_cfg64x8<128, BN, 4>(p, s); break;
     case 2: launch_cfg64<64, BN>(p, s); break;
     default: launch_cfg<128, BN, 3>(p, s); break;
   }
