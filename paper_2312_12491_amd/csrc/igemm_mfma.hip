@@ -249,7 +249,9 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma_kernel(IgemmParams p, int m
 // cores can consume.  Weights keep their fragment-packed global layout, so a block's slice of a stage
 // is BN/16 contiguous 2 KB runs that land in LDS in fragment order (conflict-free 16-byte reads).
 // ---------------------------------------------------------------------------------------------------
-template <int BM, int BN>
+// NS = register sets = prefetch distance + 1 (2 for the long-K layers, 4 for short K where a block's whole K range is
+// a handful of stages and the load latency would otherwise be paid once per stage).
+template <int BM, int BN, int NS>
 __global__ __launch_bounds__(256, 2) void igemm_mfma64_kernel(IgemmParams p, int mtiles, int ksteps_total,
                                                               int stages_per_split) {
   constexpr int WM = 2, WN = 2;
@@ -317,8 +319,8 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma64_kernel(IgemmParams p, int
     l_kx = tap - l_ky * p.ksize;
   }
 
-  u32x4 areg[2][NLA], breg[2][NLB];
-  unsigned okm[2];
+  u32x4 areg[NS][NLA], breg[NS][NLB];
+  unsigned okm[NS];
   auto load = [&](auto setc) {
     constexpr int set = decltype(setc)::value;
     const char* src;
@@ -367,7 +369,7 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma64_kernel(IgemmParams p, int
 #pragma unroll
     for (int i = 0; i < NLB; ++i) *(u32x4*)(sb + (tid + i * 256) * 16) = breg[set][i];
     __syncthreads();
-    load(IC<set ^ 1>{});
+    load(IC<(set + NS - 1) % NS>{});
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
       bf16x8 af[MT], bfr[NT];
@@ -386,10 +388,17 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma64_kernel(IgemmParams p, int
   };
 
   load(IC<0>{});
-  for (int base = 0; base < nstages; base += 2) {
+  if constexpr (NS > 2) { load(IC<1>{}); load(IC<2>{}); }
+  for (int base = 0; base < nstages; base += NS) {
     stage(IC<0>{});
     if (base + 1 >= nstages) break;
     stage(IC<1>{});
+    if constexpr (NS > 2) {
+      if (base + 2 >= nstages) break;
+      stage(IC<2>{});
+      if (base + 3 >= nstages) break;
+      stage(IC<3>{});
+    }
   }
   epilogue<MT, NT>(p, acc, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo);
 }
@@ -617,11 +626,11 @@ template <int BM, int BN, int NSETS> void launch_cfg(const IgemmParams& p, hipSt
   }
 }
 
-template <int BM, int BN> void launch_cfg64(const IgemmParams& p, hipStream_t s) {
+template <int BM, int BN, int NS> void launch_cfg64(const IgemmParams& p, hipStream_t s) {
   constexpr int LDS = 2 * (BM * 144 + BN * 128);
   static bool attr_set = false;
   if (!attr_set) {
-    hipFuncSetAttribute((const void*)igemm_mfma64_kernel<BM, BN>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    hipFuncSetAttribute((const void*)igemm_mfma64_kernel<BM, BN, NS>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     attr_set = true;
   }
   const int mtiles = (p.M + BM - 1) / BM, ntiles = (p.N + BN - 1) / BN;
@@ -630,7 +639,7 @@ template <int BM, int BN> void launch_cfg64(const IgemmParams& p, hipStream_t s)
   const int splitk = p.splitk > 1 ? p.splitk : 1;
   const int sps = (total_stages + splitk - 1) / splitk;
   dim3 grid(mtiles * ntiles, 1, splitk);
-  hipLaunchKernelGGL((igemm_mfma64_kernel<BM, BN>), grid, dim3(256), LDS, s, p, mtiles, ksteps_total, sps);
+  hipLaunchKernelGGL((igemm_mfma64_kernel<BM, BN, NS>), grid, dim3(256), LDS, s, p, mtiles, ksteps_total, sps);
   if (splitk > 1) {
     long long total4 = (long long)p.M * p.N / 4;
     hipLaunchKernelGGL(igemm_finalize_kernel, dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s, p);
@@ -658,7 +667,7 @@ template <int BM, int BN, int NSB> void launch_cfg64x8(const IgemmParams& p, hip
 }
 
 struct Choice { int variant, bn, splitk; };  // variant 0: 4 waves 128xBN, 1: 8 waves 128xBN, 2: 4 waves 64xBN, 3: 32-deep
-                                             // stages, 4: 8 waves with a deep weight prefetch
+                                             // stages, 4: 8 waves with a deep weight prefetch, 5: as 2 with prefetch distance 3
 
 // Tile / kernel / split-K selection.  Rules of thumb from sweeps on MI355X: a grid that leaves compute units with one
 // 4-wave block is better served by the 8-wave kernel or by 64-row tiles; grids far below the chip size split K.
@@ -676,19 +685,21 @@ Choice choose(const IgemmParams& p) {
   const long long mn = (long long)p.M * p.N;
   auto blocks = [&](int bm, int bn) { return ((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn); };
   int sk = 1;
-  if (stages <= 30) {
-    // short K (the 1x1 layers): shrink the tile rather than split K
+  if (stages <= 20) {
+    // short K (most 1x1 layers): shrink the tile rather than split K
     c.variant = 2;
     if (blocks(64, c.bn) < 512 && p.N % 64 == 0) c.bn = 64;
     const int nb = blocks(64, c.bn);
     if (nb < 256 && stages >= 16) sk = 512 / nb < stages / 8 ? 512 / nb : stages / 8;
   } else {
+    // long K: full tiles; grids below the chip size use the 8-wave kernel with a deep weight prefetch and split K
     const int nb = blocks(128, c.bn);
-    if (nb < 400) sk = (512 + nb / 2) / nb < stages / 8 ? (512 + nb / 2) / nb : stages / 8;
-    if (!may_split) sk = 1;
-    if ((long long)sk * mn > p.workspace_floats) sk = (int)(p.workspace_floats / mn);
-    if (sk < 1) sk = 1;
-    c.variant = nb * sk >= 400 ? 0 : 1;
+    if (nb >= 400) {
+      c.variant = 0;
+    } else {
+      c.variant = 4;
+      sk = (256 + nb / 2) / nb < stages / 8 ? (256 + nb / 2) / nb : stages / 8;
+    }
   }
   if (!may_split) sk = 1;
   if ((long long)sk * mn > p.workspace_floats) sk = (int)(p.workspace_floats / mn);
@@ -696,7 +707,7 @@ Choice choose(const IgemmParams& p) {
   if (const char* t = getenv("SDSTREAM_TUNE")) {  // "variant,bn,splitk" for sweeps; unsupported combinations are ignored
     int v = -1, bn = 0, sk = 0;
     if (sscanf(t, "%d,%d,%d", &v, &bn, &sk) == 3) {
-      if (v >= 0 && v <= 4 && (k64 || v == 3)) c.variant = v;
+      if (v >= 0 && v <= 5 && (k64 || v == 3)) c.variant = v;
       if ((bn == 160 || bn == 128 || bn == 64) && !(p.epilogue == EPI_GEGLU && bn == 160)) c.bn = bn;
       if (sk >= 1 && p.epilogue == EPI_NONE && p.workspace && (long long)sk * p.M * p.N <= p.workspace_floats &&
           sk <= (c.variant == 3 ? p.K / 32 : p.K / 64))
@@ -708,10 +719,11 @@ Choice choose(const IgemmParams& p) {
 
 template <int BN> void launch_bn(const IgemmParams& p, int variant, hipStream_t s) {
   switch (variant) {
-    case 0: launch_cfg64<128, BN>(p, s); break;
+    case 0: launch_cfg64<128, BN, 2>(p, s); break;
     case 1: launch_cfg64x8<128, BN, 2>(p, s); break;
     case 4: launch_cfg64x8<128, BN, 4>(p, s); break;
-    case 2: launch_cfg64<64, BN>(p, s); break;
+    case 2: launch_cfg64<64, BN, 2>(p, s); break;
+    case 5: launch_cfg64<64, BN, 4>(p, s); break;
     default: launch_cfg<128, BN, 3>(p, s); break;
   }
 }
