@@ -36,6 +36,7 @@ struct IgemmParams {
   int splitk;            // set by the MFMA launcher: number of K splits, fp32 partials [splitk][M][N] in `workspace`
   float* workspace;      // MFMA kernel only: split-K scratch (null forbids split-K)
   long long workspace_floats;
+  int xcd_chunked;       // set by the MFMA launcher: block -> tile order (see tile_of_block)
   const void* zeros;     // MFMA kernel only: >= 16 readable zero bytes (source of padded / out-of-range rows)
 };
 

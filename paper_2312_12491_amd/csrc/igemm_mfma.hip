@@ -27,11 +27,30 @@ __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + e
 
 template <int I> struct IC { static constexpr int value = I; };
 
+// Block -> tile mapping.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  In the natural
+// order (m-tile fastest) an XCD therefore sees every 8th m-tile of every weight column: the activations are split
+// over the L2s and the weights are fetched by all eight - right when the activations are the larger operand.  When
+// the weights are larger (the deep levels), `chunked` gives physical block p the logical index
+// (p % 8) * (grid / 8) + p / 8 (grid padded to a multiple of 8): every XCD then owns a contiguous run of the order,
+// i.e. whole weight columns, and a weight slab is fetched into one L2 instead of eight.
+struct TileId { int mtile, ntile, split; bool valid; };
+__device__ __forceinline__ TileId tile_of_block(int mtiles, int ntiles, int splitk, int chunked) {
+  const int per = gridDim.x >> 3;
+  const int logical = chunked ? (blockIdx.x & 7) * per + (blockIdx.x >> 3) : (int)blockIdx.x;
+  TileId t;
+  t.valid = logical < mtiles * ntiles * splitk;
+  t.mtile = logical % mtiles;
+  const int r = logical / mtiles;
+  t.ntile = r % ntiles;
+  t.split = r / ntiles;
+  return t;
+}
+
 // Epilogue shared by the kernels: lane holds channels n..n+3 (n = (gnt0+nt)*16 + 4*(lane/16)) of pixel
 // m = mbase + mt*16 + lane%16 in acc[mt][nt].
 template <int MT, int NT>
 __device__ __forceinline__ void epilogue(const IgemmParams& p, f32x4 (&acc)[MT][NT], int mbase, int gnt0, int lane,
-                                         int HWo) {
+                                         int HWo, int split) {
   const int Nout = p.epilogue == EPI_GEGLU ? p.N >> 1 : p.N;
   bf16_t* out = (bf16_t*)p.out;
   const bf16_t* res = (const bf16_t*)p.residual;
@@ -45,7 +64,7 @@ __device__ __forceinline__ void epilogue(const IgemmParams& p, f32x4 (&acc)[MT][
       for (int nt = 0; nt < NT; ++nt) {
         const int n = (gnt0 + nt) * 16 + (lane >> 4) * 4;
         if (n >= p.N) continue;
-        *(f32x4*)(p.workspace + ((long long)blockIdx.z * p.M + m) * p.N + n) = acc[mt][nt];
+        *(f32x4*)(p.workspace + ((long long)split * p.M + m) * p.N + n) = acc[mt][nt];
       }
       continue;
     }
@@ -101,7 +120,9 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma_kernel(IgemmParams p, int m
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave & 1, wn = wave >> 1;
-  const int mtile = blockIdx.x % mtiles, ntile = blockIdx.x / mtiles;
+  const TileId tile = tile_of_block(mtiles, (p.N + BN - 1) / BN, p.splitk > 1 ? p.splitk : 1, p.xcd_chunked);
+  if (!tile.valid) return;  // padding block (uniform for the whole block, before any barrier)
+  const int mtile = tile.mtile, ntile = tile.ntile;
   const int m0 = mtile * BM, n0 = ntile * BN;
   const int Ct = p.C1 + p.C2;
   const int pad = p.ksize >> 1;
@@ -133,7 +154,7 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma_kernel(IgemmParams p, int m
   }
 
   // ---- K range of this split, and the cursor of the next stage to load
-  const int stage0 = blockIdx.z * stages_per_split;
+  const int stage0 = tile.split * stages_per_split;
   int nstages = ksteps_total - stage0;
   if (nstages > stages_per_split) nstages = stages_per_split;
   int l_k32 = stage0;
@@ -239,7 +260,7 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma_kernel(IgemmParams p, int m
     }
   }
 
-  epilogue<MT, NT>(p, acc, m0 + wm * WTM, gnt0, lane, HWo);
+  epilogue<MT, NT>(p, acc, m0 + wm * WTM, gnt0, lane, HWo, tile.split);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -264,7 +285,9 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma64_kernel(IgemmParams p, int
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave & 1, wn = wave >> 1;
-  const int mtile = blockIdx.x % mtiles, ntile = blockIdx.x / mtiles;
+  const TileId tile = tile_of_block(mtiles, (p.N + BN - 1) / BN, p.splitk > 1 ? p.splitk : 1, p.xcd_chunked);
+  if (!tile.valid) return;  // padding block (uniform for the whole block, before any barrier)
+  const int mtile = tile.mtile, ntile = tile.ntile;
   const int m0 = mtile * BM, n0 = ntile * BN;
   const int Ct = p.C1 + p.C2;
   const int pad = p.ksize >> 1;
@@ -305,7 +328,7 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma64_kernel(IgemmParams p, int
   }
 
   const int total_stages = ksteps_total >> 1;
-  const int stage0 = blockIdx.z * stages_per_split;
+  const int stage0 = tile.split * stages_per_split;
   int nstages = total_stages - stage0;
   if (nstages > stages_per_split) nstages = stages_per_split;
   int l_stage = stage0;
@@ -400,7 +423,7 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma64_kernel(IgemmParams p, int
       stage(IC<3>{});
     }
   }
-  epilogue<MT, NT>(p, acc, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo);
+  epilogue<MT, NT>(p, acc, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo, tile.split);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -426,7 +449,9 @@ __global__ __launch_bounds__(512) void igemm_mfma64x8_kernel(IgemmParams p, int 
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int kgrp = wave >> 2, wm = wave & 1, wn = (wave >> 1) & 1;
-  const int mtile = blockIdx.x % mtiles, ntile = blockIdx.x / mtiles;
+  const TileId tile = tile_of_block(mtiles, (p.N + BN - 1) / BN, p.splitk > 1 ? p.splitk : 1, p.xcd_chunked);
+  if (!tile.valid) return;  // padding block (uniform for the whole block, before any barrier)
+  const int mtile = tile.mtile, ntile = tile.ntile;
   const int m0 = mtile * BM, n0 = ntile * BN;
   const int Ct = p.C1 + p.C2;
   const int pad = p.ksize >> 1;
@@ -467,7 +492,7 @@ __global__ __launch_bounds__(512) void igemm_mfma64x8_kernel(IgemmParams p, int 
   }
 
   const int total_stages = ksteps_total >> 1;
-  const int stage0 = blockIdx.z * stages_per_split;
+  const int stage0 = tile.split * stages_per_split;
   int nstages = total_stages - stage0;
   if (nstages > stages_per_split) nstages = stages_per_split;
   const int stage_last = total_stages - 1;
@@ -588,7 +613,7 @@ __global__ __launch_bounds__(512) void igemm_mfma64x8_kernel(IgemmParams p, int 
         for (int nt = 0; nt < NT; ++nt) acc[half * (MT / 2) + mt][nt] += red[(mt * NT + nt) * 64];
     }
   }
-  if (kgrp == 0) epilogue<MT, NT>(p, acc, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo);
+  if (kgrp == 0) epilogue<MT, NT>(p, acc, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo, tile.split);
 }
 
 // split-K finalize: sum of the partials (fp32 [splitk][M][N]) -> out with the epilogue of the main kernel
@@ -618,7 +643,7 @@ template <int BM, int BN, int NSETS> void launch_cfg(const IgemmParams& p, hipSt
   const int ksteps_total = p.K / 32;
   const int splitk = p.splitk > 1 ? p.splitk : 1;
   const int sps = (ksteps_total + splitk - 1) / splitk;
-  dim3 grid(mtiles * ntiles, 1, splitk);
+  dim3 grid((mtiles * ntiles * splitk + 7) & ~7);
   hipLaunchKernelGGL((igemm_mfma_kernel<BM, BN, NSETS>), grid, dim3(256), 0, s, p, mtiles, ksteps_total, sps);
   if (splitk > 1) {
     long long total4 = (long long)p.M * p.N / 4;
@@ -638,7 +663,7 @@ template <int BM, int BN, int NS> void launch_cfg64(const IgemmParams& p, hipStr
   const int total_stages = ksteps_total / 2;
   const int splitk = p.splitk > 1 ? p.splitk : 1;
   const int sps = (total_stages + splitk - 1) / splitk;
-  dim3 grid(mtiles * ntiles, 1, splitk);
+  dim3 grid((mtiles * ntiles * splitk + 7) & ~7);
   hipLaunchKernelGGL((igemm_mfma64_kernel<BM, BN, NS>), grid, dim3(256), LDS, s, p, mtiles, ksteps_total, sps);
   if (splitk > 1) {
     long long total4 = (long long)p.M * p.N / 4;
@@ -658,7 +683,7 @@ template <int BM, int BN, int NSB> void launch_cfg64x8(const IgemmParams& p, hip
   const int total_stages = ksteps_total / 2;
   const int splitk = p.splitk > 1 ? p.splitk : 1;
   const int sps = (total_stages + splitk - 1) / splitk;
-  dim3 grid(mtiles * ntiles, 1, splitk);
+  dim3 grid((mtiles * ntiles * splitk + 7) & ~7);
   hipLaunchKernelGGL((igemm_mfma64x8_kernel<BM, BN, NSB>), grid, dim3(512), LDS, s, p, mtiles, ksteps_total, sps);
   if (splitk > 1) {
     long long total4 = (long long)p.M * p.N / 4;
@@ -748,6 +773,7 @@ void launch_igemm_mfma(const IgemmParams& p0, hipStream_t s) {
   IgemmParams p = p0;
   const Choice c = choose(p);
   p.splitk = c.splitk;
+  p.xcd_chunked = (long long)p.N * p.K > (long long)p.M * (p.C1 + p.C2) ? 1 : 0;
   if (c.bn == 160) launch_bn<160>(p, c.variant, s);
   else if (c.bn == 128) launch_bn<128>(p, c.variant, s);
   else launch_bn<64>(p, c.variant, s);
