@@ -616,6 +616,165 @@ __global__ __launch_bounds__(512) void igemm_mfma64x8_kernel(IgemmParams p, int 
   if (kgrp == 0) epilogue<MT, NT>(p, acc, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo, tile.split);
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Variant with direct global -> LDS loads (global_load_lds_dwordx4): no staging registers, no ds_write
+// phase.  One wave-wide load moves 1 KB: lane l's 16 bytes land at (wave-uniform LDS base) + 16 l, while the
+// global address is free per lane.  Weights: one load per packed fragment (already in ds_read order).
+// Activations: one load covers 8 rows of 128 bytes (64 channels); rows are unpadded, so lane (row r, slot j)
+// fetches the row's 16-byte chunk j ^ ((r >> 1) & 7) and the fragment reads apply the same XOR, which spreads
+// the 16 rows of a fragment over all banks.  Rows outside the image or past M read the zero page instead.
+// ---------------------------------------------------------------------------------------------------
+template <int BM, int BN>
+__global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mtiles, int ksteps_total,
+                                                           int stages_per_split) {
+  constexpr int WM = 2, WN = 2;
+  constexpr int WTM = BM / WM, WTN = BN / WN, MT = WTM / 16, NT = WTN / 16;
+  constexpr int NLA = BM / 32;            // 1 KB loads of A per wave and stage
+  constexpr int NLB = BN / 32;            // 1 KB loads of B per wave and stage (BN/16 n-tiles x 2 k-steps over 4 waves)
+  constexpr int ABYTES = BM * 128, BBYTES = BN * 128, STAGE = ABYTES + BBYTES;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // 2 stages of [A | B]
+  typedef const __attribute__((address_space(1))) void* gptr_t;
+  typedef __attribute__((address_space(3))) void* lptr_t;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave & 1, wn = wave >> 1;
+  const TileId tile = tile_of_block(mtiles, (p.N + BN - 1) / BN, p.splitk > 1 ? p.splitk : 1, p.xcd_chunked);
+  if (!tile.valid) return;  // padding block (uniform for the whole block, before any barrier)
+  const int m0 = tile.mtile * BM, n0 = tile.ntile * BN;
+  const int Ct = p.C1 + p.C2;
+  const int pad = p.ksize >> 1;
+  const int HWo = p.Hout * p.Wout;
+  const int Hs = p.upsample ? p.Hin * 2 : p.Hin, Wsz = p.upsample ? p.Win * 2 : p.Win;
+  const int ups = p.upsample;
+  const char* s1 = (const char*)p.src1;
+  const char* s2 = (const char*)p.src2;
+  const char* Wp = (const char*)p.W;
+  const char* zeros = (const char*)p.zeros;
+
+  // A loads of this lane: load i of wave w fills LDS rows (i*4 + w)*8 .. +7
+  int ld_y[NLA], ld_x[NLA];
+  unsigned ld_pix0[NLA], ld_ch[NLA];
+  bool ld_ok[NLA];
+#pragma unroll
+  for (int i = 0; i < NLA; ++i) {
+    const int row = (i * 4 + wave) * 8 + (lane >> 3);
+    ld_ch[i] = (unsigned)(((lane & 7) ^ ((row >> 1) & 7)) * 8);   // first channel of the chunk this lane fetches
+    const int m = m0 + row;
+    ld_ok[i] = m < p.M;
+    const int mm = ld_ok[i] ? m : 0;
+    const int n = mm / HWo;
+    const int r = mm - n * HWo;
+    const int oy = r / p.Wout, ox = r - oy * p.Wout;
+    ld_y[i] = oy * p.stride - pad;
+    ld_x[i] = ox * p.stride - pad;
+    ld_pix0[i] = (unsigned)n * (unsigned)(p.Hin * p.Win);
+  }
+  // B loads: load i of wave w is fragment f = i*4 + w of the stage: n-tile f/2, k-step f%2
+  const int gnt_blk = n0 >> 4, ntiles_total = p.N >> 4;
+  unsigned boff[NLB];
+#pragma unroll
+  for (int i = 0; i < NLB; ++i) {
+    const int f = i * 4 + wave;
+    int g = gnt_blk + (f >> 1);
+    if (g >= ntiles_total) g = ntiles_total - 1;  // columns past N are computed on valid data and dropped
+    boff[i] = ((unsigned)g * (unsigned)ksteps_total * 64u + (unsigned)((f & 1) * 64 + lane)) * 16u;
+  }
+
+  const int total_stages = ksteps_total >> 1;
+  const int stage0 = tile.split * stages_per_split;
+  int nstages = total_stages - stage0;
+  if (nstages > stages_per_split) nstages = stages_per_split;
+  int l_stage = stage0;
+  const int stage_last = total_stages - 1;
+  int l_c, l_ky, l_kx;
+  {
+    int kk = stage0 * 64;
+    int tap = kk / Ct;
+    l_c = kk - tap * Ct;
+    l_ky = tap / p.ksize;
+    l_kx = tap - l_ky * p.ksize;
+  }
+
+  // issues the loads of the cursor's stage into LDS buffer `buf` and advances the cursor.  Past the last stage
+  // the tap index runs out of the kernel window, every row reads the zero page, and the weight stage is clamped.
+  auto issue = [&](int buf) {
+    unsigned char* sa = lds + buf * STAGE;
+    const char* src;
+    int Cs, c = l_c;
+    if (c < p.C1) { src = s1; Cs = p.C1; } else { src = s2; Cs = p.C2; c -= p.C1; }
+    const bool live = l_ky < p.ksize;
+#pragma unroll
+    for (int i = 0; i < NLA; ++i) {
+      int iy = ld_y[i] + l_ky, ix = ld_x[i] + l_kx;
+      const bool ok = live && ld_ok[i] && (unsigned)iy < (unsigned)Hs && (unsigned)ix < (unsigned)Wsz;
+      // the offset of a row that is not ok is meaningless and never used; it is computed unconditionally (and made
+      // opaque) so that the choice below is a select, not a branch around the arithmetic
+      unsigned off = ((ld_pix0[i] + (unsigned)((iy >> ups) * p.Win + (ix >> ups))) * (unsigned)Cs + (unsigned)c + ld_ch[i]) * 2u;
+      asm volatile("" : "+v"(off));
+      const char* g = ok ? src + off : zeros;
+      __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)(sa + (i * 4 + wave) * 1024), 16, 0, 0);
+    }
+    const unsigned kb = (unsigned)min(l_stage, stage_last) * 2048u;
+#pragma unroll
+    for (int i = 0; i < NLB; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(Wp + (boff[i] + kb)), (lptr_t)(sa + ABYTES + (i * 4 + wave) * 1024), 16,
+                                       0, 0);
+    ++l_stage;
+    l_c += 64;
+    const int wrap_c = l_c >= Ct ? 1 : 0;
+    l_c = wrap_c ? 0 : l_c;
+    l_kx += wrap_c;
+    const int wrap_x = l_kx == p.ksize ? 1 : 0;
+    l_kx = wrap_x ? 0 : l_kx;
+    l_ky += wrap_x;
+  };
+
+  f32x4 acc[MT][NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // fragment read addresses of this lane (row and XOR term are the same for both k-steps)
+  int a_row[MT], a_x[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    const int r = wm * WTM + mt * 16 + (lane & 15);
+    a_row[mt] = r * 128;
+    a_x[mt] = (r >> 1) & 7;
+  }
+
+  issue(0);
+  int buf = 0;
+  for (int s = 0; s < nstages; ++s) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's loads of stage s have landed
+    __syncthreads();                     // ... and everyone else's; all waves are done reading the other buffer
+    const unsigned char* sa = lds + buf * STAGE;
+    const unsigned char* sb = sa + ABYTES;
+    bf16x8 af[2][MT], bfr[2][NT];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        af[ks][mt] = *(const bf16x8*)(sa + a_row[mt] + (((ks * 4 + (lane >> 4)) ^ a_x[mt]) << 4));
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) bfr[ks][nt] = *(const bf16x8*)(sb + ((wn * NT + nt) * 2 + ks) * 1024 + lane * 16);
+    }
+    issue(buf ^ 1);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[ks][nt], af[ks][mt], acc[mt][nt], 0, 0, 0);
+    buf ^= 1;
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // the last prefetch must land before the block's LDS is released
+  epilogue<MT, NT>(p, acc, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo, tile.split);
+}
+
 // split-K finalize: sum of the partials (fp32 [splitk][M][N]) -> out with the epilogue of the main kernel
 __global__ __launch_bounds__(256) void igemm_finalize_kernel(IgemmParams p) {
   const long long idx4 = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -691,6 +850,26 @@ template <int BM, int BN, int NSB> void launch_cfg64x8(const IgemmParams& p, hip
   }
 }
 
+template <int BM, int BN> void launch_dma(const IgemmParams& p, hipStream_t s) {
+  constexpr int LDS = 2 * (BM + BN) * 128;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipFuncSetAttribute((const void*)igemm_dma_kernel<BM, BN>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    attr_set = true;
+  }
+  const int mtiles = (p.M + BM - 1) / BM, ntiles = (p.N + BN - 1) / BN;
+  const int ksteps_total = p.K / 32;
+  const int total_stages = ksteps_total / 2;
+  const int splitk = p.splitk > 1 ? p.splitk : 1;
+  const int sps = (total_stages + splitk - 1) / splitk;
+  dim3 grid((mtiles * ntiles * splitk + 7) & ~7);
+  hipLaunchKernelGGL((igemm_dma_kernel<BM, BN>), grid, dim3(256), LDS, s, p, mtiles, ksteps_total, sps);
+  if (splitk > 1) {
+    long long total4 = (long long)p.M * p.N / 4;
+    hipLaunchKernelGGL(igemm_finalize_kernel, dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s, p);
+  }
+}
+
 struct Choice { int variant, bn, splitk; };  // variant 0: 4 waves 128xBN, 1: 8 waves 128xBN, 2: 4 waves 64xBN, 3: 32-deep
                                              // stages, 4: 8 waves with a deep weight prefetch, 5: as 2 with prefetch distance 3
 
@@ -732,7 +911,7 @@ Choice choose(const IgemmParams& p) {
   if (const char* t = getenv("SDSTREAM_TUNE")) {  // "variant,bn,splitk" for sweeps; unsupported combinations are ignored
     int v = -1, bn = 0, sk = 0;
     if (sscanf(t, "%d,%d,%d", &v, &bn, &sk) == 3) {
-      if (v >= 0 && v <= 5 && (k64 || v == 3)) c.variant = v;
+      if (v >= 0 && v <= 7 && (k64 || v == 3)) c.variant = v;
       if ((bn == 160 || bn == 128 || bn == 64) && !(p.epilogue == EPI_GEGLU && bn == 160)) c.bn = bn;
       if (sk >= 1 && p.epilogue == EPI_NONE && p.workspace && (long long)sk * p.M * p.N <= p.workspace_floats &&
           sk <= (c.variant == 3 ? p.K / 32 : p.K / 64))
@@ -749,6 +928,8 @@ template <int BN> void launch_bn(const IgemmParams& p, int variant, hipStream_t 
     case 4: launch_cfg64x8<128, BN, 4>(p, s); break;
     case 2: launch_cfg64<64, BN, 2>(p, s); break;
     case 5: launch_cfg64<64, BN, 4>(p, s); break;
+    case 6: launch_dma<128, BN>(p, s); break;
+    case 7: launch_dma<64, BN>(p, s); break;
     default: launch_cfg<128, BN, 3>(p, s); break;
   }
 }
@@ -773,6 +954,11 @@ void launch_igemm_mfma(const IgemmParams& p0, hipStream_t s) {
   IgemmParams p = p0;
   const Choice c = choose(p);
   p.splitk = c.splitk;
+  if (p.splitk > 1) {  // drop splits that the rounding of stages per split leaves empty
+    const int stages = c.variant == 3 ? p.K / 32 : p.K / 64;
+    const int sps = (stages + p.splitk - 1) / p.splitk;
+    p.splitk = (stages + sps - 1) / sps;
+  }
   p.xcd_chunked = (long long)p.N * p.K > (long long)p.M * (p.C1 + p.C2) ? 1 : 0;
   if (c.bn == 160) launch_bn<160>(p, c.variant, s);
   else if (c.bn == 128) launch_bn<128>(p, c.variant, s);
