@@ -40,7 +40,7 @@ struct IgemmParams {
   const void* zeros;     // MFMA kernel only: >= 16 readable zero bytes (source of padded / out-of-range rows)
 };
 
-#define GN_MAX_SPLIT 512
+#define GN_MAX_SPLIT 64
 struct GroupNormParams {
   const void* src1;
   const void* src2;
@@ -50,7 +50,6 @@ struct GroupNormParams {
   const float* gamma;
   const float* beta;
   float* stats;  // scratch, [samples][GN_MAX_SPLIT][groups][2] floats: partial sums, or mean / rstd per (sample, group)
-  float* meanrstd;  // [samples][groups][2]
   void* out;     // [samples][HW][C1+C2]
 };
 

@@ -345,7 +345,6 @@ struct Builder {
     GroupNormParams& p = op.gn;
     p.src1 = s1; p.src2 = s2; p.C1 = C1; p.C2 = C2; p.HW = HW; p.groups = e.cfg.norm_groups;
     p.eps = eps; p.silu = silu; p.gamma = gamma; p.beta = beta; p.stats = stats;
-    p.meanrstd = (float*)(e.persist + meanrstd_off);
     p.out = aalloc((size_t)HW * (C1 + C2));
     op.rows_per_sample = HW;
     op.bytes_per_row = 2.0 * HW * (C1 + C2) * e.elt;
@@ -414,7 +413,7 @@ struct Builder {
   }
 
   float* stats_buf() { return (float*)(e.persist + stats_off); }
-  size_t stats_off = 0, meanrstd_off = 0;
+  size_t stats_off = 0;
 
   // x = concat(x1, x2) (x2 may be null); consumes nothing, returns a new buffer
   void* res_block(const std::string& name, const void* x1, int c1in, const void* x2, int c2in, int cout, int H, int W) {
@@ -533,7 +532,6 @@ struct Builder {
     e.off_sel_zero = palloc((size_t)e.max_batch * 4);
     e.off_sel_step = palloc((size_t)e.max_batch * 4);
     stats_off = palloc((size_t)e.max_batch * GN_MAX_SPLIT * c.norm_groups * 2 * 4);
-    meanrstd_off = palloc((size_t)e.max_batch * c.norm_groups * 2 * 4);
     const size_t rows_state = (size_t)c.n_streams * c.n_denoise;
     for (int i = 0; i < 2; ++i) {
       e.off_x[i] = palloc((size_t)e.max_batch * e.E * 4);

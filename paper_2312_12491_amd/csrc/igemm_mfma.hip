@@ -23,7 +23,20 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+// GELU(x) = x/2 (1 + erf(x/sqrt 2)) for the bf16 path.  erfc(|z|) from the rational approximation 7.1.26 of
+// Abramowitz & Stegun (absolute error of erf below 1.5e-7, far under bf16 resolution): E = poly(t) exp(-z^2),
+// t = 1/(1 + p|z|); 1 + erf(z) is E for z < 0 (no cancellation in the tail) and 2 - E otherwise.  About a third
+// of the instructions of erff, which made the GEGLU epilogue the longest phase of the short-K feed-forward GEMMs.
+__device__ __forceinline__ float gelu_erf(float x) {
+  const float z = fabsf(x) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
+  float poly = fmaf(1.061405429f, t, -1.453152027f);
+  poly = fmaf(poly, t, 1.421413741f);
+  poly = fmaf(poly, t, -0.284496736f);
+  poly = fmaf(poly, t, 0.254829592f);
+  const float e = poly * t * __builtin_amdgcn_exp2f(z * z * -1.4426950408889634f);
+  return 0.5f * x * (x < 0.f ? e : 2.0f - e);
+}
 
 template <int I> struct IC { static constexpr int value = I; };
 
@@ -617,24 +630,43 @@ __global__ __launch_bounds__(512) void igemm_mfma64x8_kernel(IgemmParams p, int 
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Variant with direct global -> LDS loads (global_load_lds_dwordx4): no staging registers, no ds_write
+// Kernel with direct global -> LDS loads (global_load_lds_dwordx4): no staging registers, no ds_write
 // phase.  One wave-wide load moves 1 KB: lane l's 16 bytes land at (wave-uniform LDS base) + 16 l, while the
 // global address is free per lane.  Weights: one load per packed fragment (already in ds_read order).
 // Activations: one load covers 8 rows of 128 bytes (64 channels); rows are unpadded, so lane (row r, slot j)
 // fetches the row's 16-byte chunk j ^ ((r >> 1) & 7) and the fragment reads apply the same XOR, which spreads
 // the 16 rows of a fragment over all banks.  Rows outside the image or past M read the zero page instead.
+//
+// Pipeline (two LDS buffers, loads two stages ahead): a wave reads ALL fragments of stage s into registers,
+// the block synchronises, and the buffer is immediately refilled with stage s+2 while the MFMAs of stage s
+// run; stage s+1 is already in flight in the other buffer.  The loads are issued from inline assembly and
+// waited for with explicit vmcnt values (every wave issues the same number per stage), because the compiler
+// would otherwise drain all outstanding loads before each LDS read.
 // ---------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void lds_dma16(const void* gsrc, unsigned lds_base) {
+  // m0 = wave-uniform LDS byte address of lane 0's destination; saved and restored around the load
+  unsigned keep;
+  asm volatile(
+      "s_mov_b32 %0, m0\n\t"
+      "s_mov_b32 m0, %1\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %2, off\n\t"
+      "s_mov_b32 m0, %0"
+      : "=&s"(keep)
+      : "s"(lds_base), "v"(gsrc)
+      : "memory");
+}
+
 template <int BM, int BN>
 __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mtiles, int ksteps_total,
                                                            int stages_per_split) {
-  constexpr int WM = 2, WN = 2;
+  constexpr int WM = 2, WN = 2, NW = 4;
   constexpr int WTM = BM / WM, WTN = BN / WN, MT = WTM / 16, NT = WTN / 16;
-  constexpr int NLA = BM / 32;            // 1 KB loads of A per wave and stage
-  constexpr int NLB = BN / 32;            // 1 KB loads of B per wave and stage (BN/16 n-tiles x 2 k-steps over 4 waves)
+  constexpr int NLA = BM / 8 / NW, NLB = BN / 8 / NW;   // 1 KB loads per wave and stage: activation row groups, weight fragments
+  static_assert(BM % 32 == 0 && BN % 32 == 0, "loads must divide evenly over the waves");
+  constexpr int NLOADS = NLA + NLB;
   constexpr int ABYTES = BM * 128, BBYTES = BN * 128, STAGE = ABYTES + BBYTES;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // 2 stages of [A | B]
-  typedef const __attribute__((address_space(1))) void* gptr_t;
-  typedef __attribute__((address_space(3))) void* lptr_t;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -651,14 +683,15 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
   const char* s2 = (const char*)p.src2;
   const char* Wp = (const char*)p.W;
   const char* zeros = (const char*)p.zeros;
+  const unsigned lds0 = (unsigned)(unsigned long long)(__attribute__((address_space(3))) void*)lds;
 
-  // A loads of this lane: load i of wave w fills LDS rows (i*4 + w)*8 .. +7
+  // A loads of this lane: load i of wave w fills LDS rows (i*NW + w)*8 .. +7
   int ld_y[NLA], ld_x[NLA];
   unsigned ld_pix0[NLA], ld_ch[NLA];
   bool ld_ok[NLA];
 #pragma unroll
   for (int i = 0; i < NLA; ++i) {
-    const int row = (i * 4 + wave) * 8 + (lane >> 3);
+    const int row = (i * NW + wave) * 8 + (lane >> 3);
     ld_ch[i] = (unsigned)(((lane & 7) ^ ((row >> 1) & 7)) * 8);   // first channel of the chunk this lane fetches
     const int m = m0 + row;
     ld_ok[i] = m < p.M;
@@ -670,12 +703,12 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
     ld_x[i] = ox * p.stride - pad;
     ld_pix0[i] = (unsigned)n * (unsigned)(p.Hin * p.Win);
   }
-  // B loads: load i of wave w is fragment f = i*4 + w of the stage: n-tile f/2, k-step f%2
+  // B loads: load i of wave w is fragment f = i*NW + w of the stage: n-tile f/2, k-step f%2
   const int gnt_blk = n0 >> 4, ntiles_total = p.N >> 4;
   unsigned boff[NLB];
 #pragma unroll
   for (int i = 0; i < NLB; ++i) {
-    const int f = i * 4 + wave;
+    const int f = i * NW + wave;
     int g = gnt_blk + (f >> 1);
     if (g >= ntiles_total) g = ntiles_total - 1;  // columns past N are computed on valid data and dropped
     boff[i] = ((unsigned)g * (unsigned)ksteps_total * 64u + (unsigned)((f & 1) * 64 + lane)) * 16u;
@@ -696,38 +729,45 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
     l_kx = tap - l_ky * p.ksize;
   }
 
-  // issues the loads of the cursor's stage into LDS buffer `buf` and advances the cursor.  Past the last stage
-  // the tap index runs out of the kernel window, every row reads the zero page, and the weight stage is clamped.
-  auto issue = [&](int buf) {
-    unsigned char* sa = lds + buf * STAGE;
-    const char* src;
-    int Cs, c = l_c;
-    if (c < p.C1) { src = s1; Cs = p.C1; } else { src = s2; Cs = p.C2; c -= p.C1; }
+  // per-lane source pixel and validity of every A load for the cursor's tap; recomputed when the tap changes.
+  // Past the last stage the tap index leaves the kernel window and every row reads the zero page.
+  unsigned lin[NLA];
+  bool okv[NLA];
+  auto set_tap = [&]() {
     const bool live = l_ky < p.ksize;
 #pragma unroll
     for (int i = 0; i < NLA; ++i) {
-      int iy = ld_y[i] + l_ky, ix = ld_x[i] + l_kx;
-      const bool ok = live && ld_ok[i] && (unsigned)iy < (unsigned)Hs && (unsigned)ix < (unsigned)Wsz;
-      // the offset of a row that is not ok is meaningless and never used; it is computed unconditionally (and made
-      // opaque) so that the choice below is a select, not a branch around the arithmetic
-      unsigned off = ((ld_pix0[i] + (unsigned)((iy >> ups) * p.Win + (ix >> ups))) * (unsigned)Cs + (unsigned)c + ld_ch[i]) * 2u;
+      const int iy = ld_y[i] + l_ky, ix = ld_x[i] + l_kx;
+      okv[i] = live && ld_ok[i] && (unsigned)iy < (unsigned)Hs && (unsigned)ix < (unsigned)Wsz;
+      lin[i] = ld_pix0[i] + (unsigned)((iy >> ups) * p.Win + (ix >> ups));   // meaningless (and unused) if !okv
+    }
+  };
+  set_tap();
+
+  // issues the NLOADS loads of the cursor's stage into LDS buffer `buf` and advances the cursor
+  auto issue = [&](int buf) {
+    const unsigned sa = lds0 + buf * STAGE;
+    const char* src;
+    int Cs, c = l_c;
+    if (c < p.C1) { src = s1; Cs = p.C1; } else { src = s2; Cs = p.C2; c -= p.C1; }
+#pragma unroll
+    for (int i = 0; i < NLA; ++i) {
+      // computed unconditionally (and made opaque) so that the choice below is a select, not a branch
+      unsigned off = (lin[i] * (unsigned)Cs + (unsigned)c + ld_ch[i]) * 2u;
       asm volatile("" : "+v"(off));
-      const char* g = ok ? src + off : zeros;
-      __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)(sa + (i * 4 + wave) * 1024), 16, 0, 0);
+      const char* g = okv[i] ? src + off : zeros;
+      lds_dma16(g, sa + (i * NW + wave) * 1024);
     }
     const unsigned kb = (unsigned)min(l_stage, stage_last) * 2048u;
 #pragma unroll
-    for (int i = 0; i < NLB; ++i)
-      __builtin_amdgcn_global_load_lds((gptr_t)(Wp + (boff[i] + kb)), (lptr_t)(sa + ABYTES + (i * 4 + wave) * 1024), 16,
-                                       0, 0);
+    for (int i = 0; i < NLB; ++i) lds_dma16(Wp + (boff[i] + kb), sa + ABYTES + (i * NW + wave) * 1024);
     ++l_stage;
     l_c += 64;
-    const int wrap_c = l_c >= Ct ? 1 : 0;
-    l_c = wrap_c ? 0 : l_c;
-    l_kx += wrap_c;
-    const int wrap_x = l_kx == p.ksize ? 1 : 0;
-    l_kx = wrap_x ? 0 : l_kx;
-    l_ky += wrap_x;
+    if (l_c >= Ct) {
+      l_c = 0;
+      if (++l_kx == p.ksize) { l_kx = 0; ++l_ky; }
+      set_tap();
+    }
   };
 
   f32x4 acc[MT][NT];
@@ -746,10 +786,12 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
   }
 
   issue(0);
+  issue(1);
   int buf = 0;
   for (int s = 0; s < nstages; ++s) {
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's loads of stage s have landed
-    __syncthreads();                     // ... and everyone else's; all waves are done reading the other buffer
+    // vmcnt(NLOADS): all but this wave's newest NLOADS loads (stage s+1) have landed, i.e. stage s has
+    __builtin_amdgcn_s_waitcnt(0x0F70 | NLOADS);
+    __syncthreads();                     // ... and everyone else's part of stage s too
     const unsigned char* sa = lds + buf * STAGE;
     const unsigned char* sb = sa + ABYTES;
     bf16x8 af[2][MT], bfr[2][NT];
@@ -761,7 +803,8 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) bfr[ks][nt] = *(const bf16x8*)(sb + ((wn * NT + nt) * 2 + ks) * 1024 + lane * 16);
     }
-    issue(buf ^ 1);
+    __syncthreads();                     // every wave holds its fragments: the buffer can be refilled
+    issue(buf);                          // stage s+2
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
@@ -771,7 +814,7 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
           acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[ks][nt], af[ks][mt], acc[mt][nt], 0, 0, 0);
     buf ^= 1;
   }
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // the last prefetch must land before the block's LDS is released
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // the prefetches past the end must land before the block's LDS is released
   epilogue<MT, NT>(p, acc, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo, tile.split);
 }
 
@@ -878,31 +921,39 @@ struct Choice { int variant, bn, splitk; };  // variant 0: 4 waves 128xBN, 1: 8 
 Choice choose(const IgemmParams& p) {
   Choice c;
   const bool k64 = p.C1 % 64 == 0 && p.C2 % 64 == 0;
-  if (p.epilogue == EPI_GEGLU) c.bn = 128;
-  else if (p.N % 160 == 0) c.bn = 160;
-  else if (p.N % 128 == 0) c.bn = 128;
-  else c.bn = 64;
+  const bool geglu = p.epilogue == EPI_GEGLU;
+  const int bn0 = geglu ? 128 : p.N % 160 == 0 ? 160 : p.N % 128 == 0 ? 128 : 64;
+  c.bn = bn0;
   c.splitk = 1;
   if (!k64) { c.variant = 3; return c; }
   const int stages = p.K / 64;
   const bool may_split = p.epilogue == EPI_NONE && p.workspace != nullptr;
   const long long mn = (long long)p.M * p.N;
   auto blocks = [&](int bm, int bn) { return ((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn); };
+  // 128-row tiles: of the widths that divide N, the one that fills whole rounds of 512 resident blocks best
+  int bn6 = bn0;
+  if (!geglu && p.N % 160 == 0 && p.N % 128 == 0) {
+    auto fill = [&](int bn) { const int nb = blocks(128, bn); return (double)nb / (double)(((nb + 511) / 512) * 512); };
+    if (fill(128) > fill(160) + 1e-3) bn6 = 128;
+  }
+  int nb128 = blocks(128, bn6);
   int sk = 1;
-  if (stages <= 20) {
-    // short K (most 1x1 layers): shrink the tile rather than split K
-    c.variant = 2;
-    if (blocks(64, c.bn) < 512 && p.N % 64 == 0) c.bn = 64;
-    const int nb = blocks(64, c.bn);
-    if (nb < 256 && stages >= 16) sk = 512 / nb < stages / 8 ? 512 / nb : stages / 8;
+  if ((stages >= 64 && (long long)stages * nb128 >= 8000) || (nb128 >= 400 && stages >= 10 && p.M >= 4096)) {
+    // long K or a grid of several rounds: full tiles, split K when the grid is below the chip size
+    c.variant = 6;
+    c.bn = nb128 >= 400 ? bn6 : bn0;
+    nb128 = blocks(128, c.bn);
+    if (nb128 < 400) sk = (512 + nb128 / 2) / nb128 < stages / 8 ? (512 + nb128 / 2) / nb128 : stages / 8;
   } else {
-    // long K: full tiles; grids below the chip size use the 8-wave kernel with a deep weight prefetch and split K
-    const int nb = blocks(128, c.bn);
-    if (nb >= 400) {
-      c.variant = 0;
+    c.variant = 7;
+    if (stages >= 32) {
+      const int nb = blocks(64, c.bn);
+      if (nb < 512) sk = 512 / nb < stages / 8 ? 512 / nb : stages / 8;
     } else {
-      c.variant = 4;
-      sk = (256 + nb / 2) / nb < stages / 8 ? (256 + nb / 2) / nb : stages / 8;
+      // short K (most 1x1 layers): shrink the tile rather than split K
+      if (blocks(64, c.bn) < 512 && p.N % 64 == 0) c.bn = 64;
+      const int nb = blocks(64, c.bn);
+      if (nb < 192 && stages >= 16) sk = 512 / nb < stages / 8 ? 512 / nb : stages / 8;
     }
   }
   if (!may_split) sk = 1;

@@ -139,36 +139,41 @@ __global__ void gn_partial_bf16_kernel(GroupNormParams p, int ppb, int nsplit, i
   }
 }
 
-// one wave per (sample, group): folds the pixel-split partials in double, fixed order
-__global__ __launch_bounds__(256) void gn_finalize_kernel(GroupNormParams p, int nsplit) {
-  const int idx = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-  if (idx >= p.samples * p.groups) return;
-  const int n = idx / p.groups, g = idx - n * p.groups;
-  const int cg = (p.C1 + p.C2) / p.groups;
-  double ss = 0.0, qq = 0.0;
-  for (int k = lane; k < nsplit; k += 64) {
-    const float* src = p.stats + (((long long)n * nsplit + k) * p.groups + g) * 2;
-    ss += src[0];
-    qq += src[1];
+// Pass 2: every block first folds the pixel-split partials of its sample into mean / rstd per group (in double,
+// fixed order, so all blocks of a sample agree bit for bit), then normalises its pixels.  `nsplit_p` is the split
+// count of pass 1 (at most 64, so the fold is a few loads per thread).
+__global__ void gn_apply_bf16_kernel(GroupNormParams p, int ppb, int nsplit, int chunks, int lanes, int nsplit_p) {
+  extern __shared__ double smd[];                 // [J][groups][2] partial folds, then [groups][2] floats: mean, rstd
+  const int C = p.C1 + p.C2, cg = C / p.groups;
+  const int n = blockIdx.x / nsplit, sp = blockIdx.x - n * nsplit;
+  const int chunk = threadIdx.x % chunks, ln = threadIdx.x / chunks;
+  const int J = 8;
+  for (int idx = threadIdx.x; idx < J * p.groups; idx += blockDim.x) {
+    const int j = idx / p.groups, g = idx - j * p.groups;
+    double ss = 0.0, qq = 0.0;
+    for (int k = j; k < nsplit_p; k += J) {
+      const float* src = p.stats + (((long long)n * nsplit_p + k) * p.groups + g) * 2;
+      ss += src[0];
+      qq += src[1];
+    }
+    smd[idx * 2] = ss;
+    smd[idx * 2 + 1] = qq;
   }
-  ss = wave_sum(ss);
-  qq = wave_sum(qq);
-  if (lane == 0) {
+  __syncthreads();
+  float* sm = (float*)(smd + J * p.groups * 2);
+  for (int g = threadIdx.x; g < p.groups; g += blockDim.x) {
+    double ss = 0.0, qq = 0.0;
+    for (int j = 0; j < J; ++j) {
+      ss += smd[(j * p.groups + g) * 2];
+      qq += smd[(j * p.groups + g) * 2 + 1];
+    }
     const double cnt = (double)p.HW * cg;
     const double mean = ss / cnt;
     double var = qq / cnt - mean * mean;
     if (var < 0) var = 0;
-    p.meanrstd[idx * 2] = (float)mean;
-    p.meanrstd[idx * 2 + 1] = (float)(1.0 / sqrt(var + (double)p.eps));
+    sm[g * 2] = (float)mean;
+    sm[g * 2 + 1] = (float)(1.0 / sqrt(var + (double)p.eps));
   }
-}
-
-__global__ void gn_apply_bf16_kernel(GroupNormParams p, int ppb, int nsplit, int chunks, int lanes) {
-  extern __shared__ float sm[];  // [groups][2]: mean, rstd
-  const int C = p.C1 + p.C2, cg = C / p.groups;
-  const int n = blockIdx.x / nsplit, sp = blockIdx.x - n * nsplit;
-  const int chunk = threadIdx.x % chunks, ln = threadIdx.x / chunks;
-  for (int i = threadIdx.x; i < p.groups * 2; i += blockDim.x) sm[i] = p.meanrstd[(long long)n * p.groups * 2 + i];
   __syncthreads();
   float sc[8], sh[8];
 #pragma unroll
@@ -202,17 +207,20 @@ void launch_gn_fast(const GroupNormParams& p, hipStream_t s) {
   const int C = p.C1 + p.C2, chunks = C / 8;
   const int lanes = chunks >= 256 ? 1 : 256 / chunks;
   const int threads = chunks * lanes;
-  long long want = ((long long)p.HW * p.samples + 1023) / 1024;  // aim for ~1024 blocks
+  // pass 1: at most 64 pixel splits per sample (one block per compute unit at 4 samples)
+  int ppb_p = (p.HW + 63) / 64;
+  if (ppb_p < 2 * lanes) ppb_p = 2 * lanes;
+  const int nsplit_p = (p.HW + ppb_p - 1) / ppb_p;
+  hipLaunchKernelGGL(gn_partial_bf16_kernel, dim3(p.samples * nsplit_p), dim3(threads),
+                     (size_t)lanes * C * 2 * sizeof(float), s, p, ppb_p, nsplit_p, chunks, lanes);
+  // pass 2: ~1024 blocks
+  long long want = ((long long)p.HW * p.samples + 1023) / 1024;
   int ppb = (int)(want < 2 * lanes ? 2 * lanes : want);
   if (ppb > 64) ppb = 64;
-  int nsplit = (p.HW + ppb - 1) / ppb;
-  if (nsplit > GN_MAX_SPLIT) { nsplit = GN_MAX_SPLIT; ppb = (p.HW + nsplit - 1) / nsplit; nsplit = (p.HW + ppb - 1) / ppb; }
-  const dim3 grid(p.samples * nsplit);
-  hipLaunchKernelGGL(gn_partial_bf16_kernel, grid, dim3(threads), (size_t)lanes * C * 2 * sizeof(float), s, p, ppb, nsplit,
-                     chunks, lanes);
-  hipLaunchKernelGGL(gn_finalize_kernel, dim3((p.samples * p.groups + 3) / 4), dim3(256), 0, s, p, nsplit);
-  hipLaunchKernelGGL(gn_apply_bf16_kernel, grid, dim3(threads), (size_t)p.groups * 2 * sizeof(float), s, p, ppb, nsplit,
-                     chunks, lanes);
+  const int nsplit = (p.HW + ppb - 1) / ppb;
+  hipLaunchKernelGGL(gn_apply_bf16_kernel, dim3(p.samples * nsplit), dim3(threads),
+                     (size_t)8 * p.groups * 2 * sizeof(double) + (size_t)p.groups * 2 * sizeof(float), s, p, ppb, nsplit,
+                     chunks, lanes, nsplit_p);
 }
 
 }  // namespace
