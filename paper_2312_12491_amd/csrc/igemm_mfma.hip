@@ -2,15 +2,18 @@
 //
 //   out[m][n] = sum_k A[m][k] W[n][k]     m = (sample, oy, ox), k = tap*(C1+C2) + c
 //
-// Work split: one 256-thread block (4 waves, 2x2) owns a BM x BN output tile.  The activation tile
-// (implicit im2col rows, gathered from NHWC with zero padding, stride, nearest-2x upsample and a second
-// concatenated source folded into the indexing) is staged through double-buffered LDS in 32-deep K stages; the weights are
-// stored pre-packed in MFMA fragment order and go from global memory straight into registers, one coalesced
-// 1 KB read per fragment.  Both are prefetched into a ring of register sets several stages ahead.  The MFMA is issued with the weight fragment as the
-// row operand, so every lane ends up with 4 consecutive output channels of one pixel: bias, time-embedding
-// bias, GEGLU and the residual are applied on registers and stored as 8-byte vectors.
-// Optional split-K (grid.z) writes fp32 partial tiles to a workspace that a small finalize kernel sums and
-// turns into the output.
+// Work split: one 256-thread block (4 waves, 2x2) owns a BM x BN output tile.  The activation tile (implicit
+// im2col rows gathered from NHWC, with zero padding, stride, nearest-2x upsample and a second, concatenated
+// source folded into the indexing) and the weight tile (stored pre-packed in MFMA fragment order) are staged
+// through double-buffered LDS.  Two kernels: the main one moves both operands global -> LDS directly in 64-deep
+// K stages (channels a multiple of 64); the other stages activations through registers in 32-deep stages and
+// reads weight fragments straight into registers (channels a multiple of 32).  The MFMA is issued with the
+// weight fragment as the row operand, so every lane ends up with 4 consecutive output channels of one pixel:
+// bias, time-embedding bias, GEGLU and the residual are applied on registers and stored as 8-byte vectors.
+// Optional split-K writes fp32 partial tiles to a workspace that a small finalize kernel sums and turns into
+// the output.  (Summing them in the last block to finish instead was measured and is slower here: the blocks of
+// a tile sit on different XCDs, and both a device-scope fence per block - a write-back of the whole L2 - and
+// cache-bypassing accesses to the partials cost more than the extra launch.)
 #include "common.h"
 
 #include <stdio.h>
@@ -277,359 +280,6 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma_kernel(IgemmParams p, int m
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Variant for channel counts that are multiples of 64: 64-deep K stages, BOTH operands through LDS.
-// Each weight fragment is fetched from global memory once per block (not once per wave row), which
-// is what bounds the other variant: the vector L1 delivers far fewer bytes per clock than the matrix
-// cores can consume.  Weights keep their fragment-packed global layout, so a block's slice of a stage
-// is BN/16 contiguous 2 KB runs that land in LDS in fragment order (conflict-free 16-byte reads).
-// ---------------------------------------------------------------------------------------------------
-// NS = register sets = prefetch distance + 1 (2 for the long-K layers, 4 for short K where a block's whole K range is
-// a handful of stages and the load latency would otherwise be paid once per stage).
-template <int BM, int BN, int NS>
-__global__ __launch_bounds__(256, 2) void igemm_mfma64_kernel(IgemmParams p, int mtiles, int ksteps_total,
-                                                              int stages_per_split) {
-  constexpr int WM = 2, WN = 2;
-  constexpr int WTM = BM / WM, WTN = BN / WN, MT = WTM / 16, NT = WTN / 16;
-  constexpr int ROWB = 144;               // A row pitch: 64 bf16 + 16 bytes pad
-  constexpr int NLA = BM * 8 / 256;       // 16-byte chunks of A per thread and stage
-  constexpr int NLB = BN * 8 / 256;       // 16-byte chunks of B per thread and stage
-  constexpr int ABYTES = BM * ROWB, BBYTES = BN * 128, STAGE = ABYTES + BBYTES;
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // 2 stages of [A | B]
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave & 1, wn = wave >> 1;
-  const TileId tile = tile_of_block(mtiles, (p.N + BN - 1) / BN, p.splitk > 1 ? p.splitk : 1, p.xcd_chunked);
-  if (!tile.valid) return;  // padding block (uniform for the whole block, before any barrier)
-  const int mtile = tile.mtile, ntile = tile.ntile;
-  const int m0 = mtile * BM, n0 = ntile * BN;
-  const int Ct = p.C1 + p.C2;
-  const int pad = p.ksize >> 1;
-  const int HWo = p.Hout * p.Wout;
-  const int Hs = p.upsample ? p.Hin * 2 : p.Hin, Wsz = p.upsample ? p.Win * 2 : p.Win;
-  const int ups = p.upsample;
-  const char* s1 = (const char*)p.src1;
-  const char* s2 = (const char*)p.src2;
-  const char* Wp = (const char*)p.W;
-
-  int ld_y[NLA], ld_x[NLA], ld_lds[NLA];
-  unsigned ld_pix0[NLA];
-  bool ld_ok[NLA];
-  const int cq = tid & 7;
-#pragma unroll
-  for (int i = 0; i < NLA; ++i) {
-    int row = (tid + i * 256) >> 3;
-    ld_lds[i] = row * ROWB + cq * 16;
-    int m = m0 + row;
-    ld_ok[i] = m < p.M;
-    int mm = ld_ok[i] ? m : 0;
-    int n = mm / HWo;
-    int r = mm - n * HWo;
-    int oy = r / p.Wout, ox = r - oy * p.Wout;
-    ld_y[i] = oy * p.stride - pad;
-    ld_x[i] = ox * p.stride - pad;
-    ld_pix0[i] = (unsigned)n * (unsigned)(p.Hin * p.Win);
-  }
-  // B chunks of this thread: chunk q = tid + i*256 -> n-tile q/128, position q%128 inside the 2 KB run
-  const int gnt_blk = n0 >> 4, ntiles_total = p.N >> 4;
-  unsigned boff[NLB];
-#pragma unroll
-  for (int i = 0; i < NLB; ++i) {
-    int q = tid + i * 256;
-    int g = gnt_blk + (q >> 7);
-    if (g >= ntiles_total) g = ntiles_total - 1;
-    boff[i] = ((unsigned)g * (unsigned)ksteps_total * 64u + (unsigned)(q & 127)) * 16u;
-  }
-
-  const int total_stages = ksteps_total >> 1;
-  const int stage0 = tile.split * stages_per_split;
-  int nstages = total_stages - stage0;
-  if (nstages > stages_per_split) nstages = stages_per_split;
-  int l_stage = stage0;
-  const int stage_last = total_stages - 1;
-  int l_c, l_ky, l_kx;
-  {
-    int kk = stage0 * 64;
-    int tap = kk / Ct;
-    l_c = kk - tap * Ct;
-    l_ky = tap / p.ksize;
-    l_kx = tap - l_ky * p.ksize;
-  }
-
-  u32x4 areg[NS][NLA], breg[NS][NLB];
-  unsigned okm[NS];
-  auto load = [&](auto setc) {
-    constexpr int set = decltype(setc)::value;
-    const char* src;
-    int Cs, c = l_c;
-    if (c < p.C1) { src = s1; Cs = p.C1; } else { src = s2; Cs = p.C2; c -= p.C1; }
-    unsigned m = 0;
-#pragma unroll
-    for (int i = 0; i < NLA; ++i) {
-      int iy = ld_y[i] + l_ky, ix = ld_x[i] + l_kx;
-      bool ok = ld_ok[i] && (unsigned)iy < (unsigned)Hs && (unsigned)ix < (unsigned)Wsz;
-      iy = min(max(iy, 0), Hs - 1) >> ups;
-      ix = min(max(ix, 0), Wsz - 1) >> ups;
-      unsigned off = ((ld_pix0[i] + (unsigned)(iy * p.Win + ix)) * (unsigned)Cs + (unsigned)(c + cq * 8)) * 2u;
-      areg[set][i] = *(const u32x4*)(src + off);
-      m |= (ok ? 1u : 0u) << i;
-    }
-    okm[set] = m;
-    const unsigned kb = (unsigned)min(l_stage, stage_last) * 2048u;
-#pragma unroll
-    for (int i = 0; i < NLB; ++i) breg[set][i] = *(const u32x4*)(Wp + (boff[i] + kb));
-    ++l_stage;
-    l_c += 64;
-    if (l_c >= Ct) {
-      l_c = 0;
-      if (++l_kx == p.ksize) { l_kx = 0; ++l_ky; }
-    }
-  };
-
-  f32x4 acc[MT][NT];
-#pragma unroll
-  for (int i = 0; i < MT; ++i)
-#pragma unroll
-    for (int j = 0; j < NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  int buf = 0;
-  auto stage = [&](auto setc) {
-    constexpr int set = decltype(setc)::value;
-    unsigned char* sa = lds + buf * STAGE;
-    unsigned char* sb = sa + ABYTES;
-#pragma unroll
-    for (int i = 0; i < NLA; ++i) {
-      u32x4 v = areg[set][i];
-      if (!((okm[set] >> i) & 1u)) v = u32x4{0u, 0u, 0u, 0u};
-      *(u32x4*)(sa + ld_lds[i]) = v;
-    }
-#pragma unroll
-    for (int i = 0; i < NLB; ++i) *(u32x4*)(sb + (tid + i * 256) * 16) = breg[set][i];
-    __syncthreads();
-    load(IC<(set + NS - 1) % NS>{});
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      bf16x8 af[MT], bfr[NT];
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        af[mt] = *(const bf16x8*)(sa + (wm * WTM + mt * 16 + (lane & 15)) * ROWB + ks * 64 + (lane >> 4) * 16);
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) bfr[nt] = *(const bf16x8*)(sb + ((wn * NT + nt) * 2 + ks) * 1024 + lane * 16);
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[nt], af[mt], acc[mt][nt], 0, 0, 0);
-    }
-    buf ^= 1;
-  };
-
-  load(IC<0>{});
-  if constexpr (NS > 2) { load(IC<1>{}); load(IC<2>{}); }
-  for (int base = 0; base < nstages; base += NS) {
-    stage(IC<0>{});
-    if (base + 1 >= nstages) break;
-    stage(IC<1>{});
-    if constexpr (NS > 2) {
-      if (base + 2 >= nstages) break;
-      stage(IC<2>{});
-      if (base + 3 >= nstages) break;
-      stage(IC<3>{});
-    }
-  }
-  epilogue<MT, NT>(p, acc, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo, tile.split);
-}
-
-// ---------------------------------------------------------------------------------------------------
-// 8-wave variant of the kernel above for grids that give a compute unit only one block.  One wave per
-// SIMD cannot issue v_mfma_f32_16x16x32_bf16 back to back (measured: 58 % of peak with 20 independent
-// accumulators, 93 % with two waves), so the block carries two wave groups that split every 64-deep
-// stage between them (k 0..31 / k 32..63 of the same 128 x BN tile) and add their accumulators through
-// LDS at the end.  Tile, traffic and LDS layout are those of the 4-wave kernel.
-// ---------------------------------------------------------------------------------------------------
-// NSB = register sets for the weight stream (prefetch distance NSB-1 stages): 2 normally, 4 for the few-row layers
-// whose time is the HBM stream of their weights.
-template <int BM, int BN, int NSB>
-__global__ __launch_bounds__(512) void igemm_mfma64x8_kernel(IgemmParams p, int mtiles, int ksteps_total,
-                                                             int stages_per_split) {
-  constexpr int WM = 2, WN = 2;
-  constexpr int WTM = BM / WM, WTN = BN / WN, MT = WTM / 16, NT = WTN / 16;
-  constexpr int ROWB = 144;
-  constexpr int NLA = BM * 8 / 512;
-  constexpr int NBCH = BN * 8;                 // 16-byte chunks of B per stage
-  constexpr int NLB = (NBCH + 511) / 512;
-  constexpr int ABYTES = BM * ROWB, BBYTES = BN * 128, STAGE = ABYTES + BBYTES;
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int kgrp = wave >> 2, wm = wave & 1, wn = (wave >> 1) & 1;
-  const TileId tile = tile_of_block(mtiles, (p.N + BN - 1) / BN, p.splitk > 1 ? p.splitk : 1, p.xcd_chunked);
-  if (!tile.valid) return;  // padding block (uniform for the whole block, before any barrier)
-  const int mtile = tile.mtile, ntile = tile.ntile;
-  const int m0 = mtile * BM, n0 = ntile * BN;
-  const int Ct = p.C1 + p.C2;
-  const int pad = p.ksize >> 1;
-  const int HWo = p.Hout * p.Wout;
-  const int Hs = p.upsample ? p.Hin * 2 : p.Hin, Wsz = p.upsample ? p.Win * 2 : p.Win;
-  const int ups = p.upsample;
-  const char* s1 = (const char*)p.src1;
-  const char* s2 = (const char*)p.src2;
-  const char* Wp = (const char*)p.W;
-
-  int ld_y[NLA], ld_x[NLA], ld_lds[NLA];
-  unsigned ld_pix0[NLA];
-  bool ld_ok[NLA];
-  const int cq = tid & 7;
-#pragma unroll
-  for (int i = 0; i < NLA; ++i) {
-    int row = (tid + i * 512) >> 3;
-    ld_lds[i] = row * ROWB + cq * 16;
-    int m = m0 + row;
-    ld_ok[i] = m < p.M;
-    int mm = ld_ok[i] ? m : 0;
-    int n = mm / HWo;
-    int r = mm - n * HWo;
-    int oy = r / p.Wout, ox = r - oy * p.Wout;
-    ld_y[i] = oy * p.stride - pad;
-    ld_x[i] = ox * p.stride - pad;
-    ld_pix0[i] = (unsigned)n * (unsigned)(p.Hin * p.Win);
-  }
-  const int gnt_blk = n0 >> 4, ntiles_total = p.N >> 4;
-  unsigned boff[NLB];
-#pragma unroll
-  for (int i = 0; i < NLB; ++i) {
-    int q = tid + i * 512;
-    if (q >= NBCH) q = NBCH - 1;  // surplus lanes repeat the last chunk (same value, same address)
-    int g = gnt_blk + (q >> 7);
-    if (g >= ntiles_total) g = ntiles_total - 1;
-    boff[i] = ((unsigned)g * (unsigned)ksteps_total * 64u + (unsigned)(q & 127)) * 16u;
-  }
-
-  const int total_stages = ksteps_total >> 1;
-  const int stage0 = tile.split * stages_per_split;
-  int nstages = total_stages - stage0;
-  if (nstages > stages_per_split) nstages = stages_per_split;
-  const int stage_last = total_stages - 1;
-  int l_c, l_ky, l_kx;
-  {
-    int kk = stage0 * 64;
-    int tap = kk / Ct;
-    l_c = kk - tap * Ct;
-    l_ky = tap / p.ksize;
-    l_kx = tap - l_ky * p.ksize;
-  }
-
-  u32x4 areg[2][NLA], breg[NSB][NLB];
-  unsigned okm[2];
-  int lb_stage = stage0;
-  auto load_a = [&](auto setc) {
-    constexpr int set = decltype(setc)::value;
-    const char* src;
-    int Cs, c = l_c;
-    if (c < p.C1) { src = s1; Cs = p.C1; } else { src = s2; Cs = p.C2; c -= p.C1; }
-    unsigned m = 0;
-#pragma unroll
-    for (int i = 0; i < NLA; ++i) {
-      int iy = ld_y[i] + l_ky, ix = ld_x[i] + l_kx;
-      bool ok = ld_ok[i] && (unsigned)iy < (unsigned)Hs && (unsigned)ix < (unsigned)Wsz;
-      iy = min(max(iy, 0), Hs - 1) >> ups;
-      ix = min(max(ix, 0), Wsz - 1) >> ups;
-      unsigned off = ((ld_pix0[i] + (unsigned)(iy * p.Win + ix)) * (unsigned)Cs + (unsigned)(c + cq * 8)) * 2u;
-      areg[set][i] = *(const u32x4*)(src + off);
-      m |= (ok ? 1u : 0u) << i;
-    }
-    okm[set] = m;
-    l_c += 64;
-    if (l_c >= Ct) {
-      l_c = 0;
-      if (++l_kx == p.ksize) { l_kx = 0; ++l_ky; }
-    }
-  };
-  auto load_b = [&](auto setc) {
-    constexpr int set = decltype(setc)::value;
-    const unsigned kb = (unsigned)min(lb_stage, stage_last) * 2048u;
-#pragma unroll
-    for (int i = 0; i < NLB; ++i) breg[set][i] = *(const u32x4*)(Wp + (boff[i] + kb));
-    ++lb_stage;
-  };
-
-  f32x4 acc[MT][NT];
-#pragma unroll
-  for (int i = 0; i < MT; ++i)
-#pragma unroll
-    for (int j = 0; j < NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  int buf = 0;
-  auto stage = [&](auto uc) {
-    constexpr int u = decltype(uc)::value;   // stage index modulo 4
-    constexpr int sa_set = u & 1, sb_set = u % NSB;
-    unsigned char* sa = lds + buf * STAGE;
-    unsigned char* sb = sa + ABYTES;
-#pragma unroll
-    for (int i = 0; i < NLA; ++i) {
-      u32x4 v = areg[sa_set][i];
-      if (!((okm[sa_set] >> i) & 1u)) v = u32x4{0u, 0u, 0u, 0u};
-      *(u32x4*)(sa + ld_lds[i]) = v;
-    }
-#pragma unroll
-    for (int i = 0; i < NLB; ++i) {
-      int q = tid + i * 512;
-      if (q >= NBCH) q = NBCH - 1;
-      *(u32x4*)(sb + q * 16) = breg[sb_set][i];
-    }
-    __syncthreads();
-    load_a(IC<sa_set ^ 1>{});
-    load_b(IC<(u + NSB - 1) % NSB>{});
-    bf16x8 af[MT], bfr[NT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-      af[mt] = *(const bf16x8*)(sa + (wm * WTM + mt * 16 + (lane & 15)) * ROWB + kgrp * 64 + (lane >> 4) * 16);
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) bfr[nt] = *(const bf16x8*)(sb + ((wn * NT + nt) * 2 + kgrp) * 1024 + lane * 16);
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[nt], af[mt], acc[mt][nt], 0, 0, 0);
-    buf ^= 1;
-  };
-
-  load_a(IC<0>{});
-  load_b(IC<0>{});
-  if constexpr (NSB > 2) { load_b(IC<1>{}); load_b(IC<2>{}); }
-  for (int base = 0; base < nstages; base += 4) {
-    stage(IC<0>{});
-    if (base + 1 >= nstages) break;
-    stage(IC<1>{});
-    if (base + 2 >= nstages) break;
-    stage(IC<2>{});
-    if (base + 3 >= nstages) break;
-    stage(IC<3>{});
-  }
-
-  // fold the second wave group into the first through LDS, two m-tiles at a time
-  static_assert(4 * (MT / 2) * NT * 1024 <= 2 * STAGE, "reduction buffer must fit in the stage buffers");
-#pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    __syncthreads();
-    f32x4* red = (f32x4*)lds + ((wave & 3) * (MT / 2) * NT) * 64 + lane;
-    if (kgrp == 1) {
-#pragma unroll
-      for (int mt = 0; mt < MT / 2; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) red[(mt * NT + nt) * 64] = acc[half * (MT / 2) + mt][nt];
-    }
-    __syncthreads();
-    if (kgrp == 0) {
-#pragma unroll
-      for (int mt = 0; mt < MT / 2; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) acc[half * (MT / 2) + mt][nt] += red[(mt * NT + nt) * 64];
-    }
-  }
-  if (kgrp == 0) epilogue<MT, NT>(p, acc, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo, tile.split);
-}
-
-// ---------------------------------------------------------------------------------------------------
 // Kernel with direct global -> LDS loads (global_load_lds_dwordx4): no staging registers, no ds_write
 // phase.  One wave-wide load moves 1 KB: lane l's 16 bytes land at (wave-uniform LDS base) + 16 l, while the
 // global address is free per lane.  Weights: one load per packed fragment (already in ds_read order).
@@ -853,46 +503,6 @@ template <int BM, int BN, int NSETS> void launch_cfg(const IgemmParams& p, hipSt
   }
 }
 
-template <int BM, int BN, int NS> void launch_cfg64(const IgemmParams& p, hipStream_t s) {
-  constexpr int LDS = 2 * (BM * 144 + BN * 128);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipFuncSetAttribute((const void*)igemm_mfma64_kernel<BM, BN, NS>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-    attr_set = true;
-  }
-  const int mtiles = (p.M + BM - 1) / BM, ntiles = (p.N + BN - 1) / BN;
-  const int ksteps_total = p.K / 32;
-  const int total_stages = ksteps_total / 2;
-  const int splitk = p.splitk > 1 ? p.splitk : 1;
-  const int sps = (total_stages + splitk - 1) / splitk;
-  dim3 grid((mtiles * ntiles * splitk + 7) & ~7);
-  hipLaunchKernelGGL((igemm_mfma64_kernel<BM, BN, NS>), grid, dim3(256), LDS, s, p, mtiles, ksteps_total, sps);
-  if (splitk > 1) {
-    long long total4 = (long long)p.M * p.N / 4;
-    hipLaunchKernelGGL(igemm_finalize_kernel, dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s, p);
-  }
-}
-
-template <int BM, int BN, int NSB> void launch_cfg64x8(const IgemmParams& p, hipStream_t s) {
-  constexpr int LDS = 2 * (BM * 144 + BN * 128);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipFuncSetAttribute((const void*)igemm_mfma64x8_kernel<BM, BN, NSB>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-    attr_set = true;
-  }
-  const int mtiles = (p.M + BM - 1) / BM, ntiles = (p.N + BN - 1) / BN;
-  const int ksteps_total = p.K / 32;
-  const int total_stages = ksteps_total / 2;
-  const int splitk = p.splitk > 1 ? p.splitk : 1;
-  const int sps = (total_stages + splitk - 1) / splitk;
-  dim3 grid((mtiles * ntiles * splitk + 7) & ~7);
-  hipLaunchKernelGGL((igemm_mfma64x8_kernel<BM, BN, NSB>), grid, dim3(512), LDS, s, p, mtiles, ksteps_total, sps);
-  if (splitk > 1) {
-    long long total4 = (long long)p.M * p.N / 4;
-    hipLaunchKernelGGL(igemm_finalize_kernel, dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s, p);
-  }
-}
-
 template <int BM, int BN> void launch_dma(const IgemmParams& p, hipStream_t s) {
   constexpr int LDS = 2 * (BM + BN) * 128;
   static bool attr_set = false;
@@ -913,11 +523,11 @@ template <int BM, int BN> void launch_dma(const IgemmParams& p, hipStream_t s) {
   }
 }
 
-struct Choice { int variant, bn, splitk; };  // variant 0: 4 waves 128xBN, 1: 8 waves 128xBN, 2: 4 waves 64xBN, 3: 32-deep
-                                             // stages, 4: 8 waves with a deep weight prefetch, 5: as 2 with prefetch distance 3
+struct Choice { int variant, bn, splitk; };  // variant 0: 32-deep stages, weights through registers (any C % 32 == 0);
+                                             // 1: direct-to-LDS kernel with 128-row tiles, 2: with 64-row tiles
 
-// Tile / kernel / split-K selection.  Rules of thumb from sweeps on MI355X: a grid that leaves compute units with one
-// 4-wave block is better served by the 8-wave kernel or by 64-row tiles; grids far below the chip size split K.
+// Tile / kernel / split-K selection, from per-layer timings of the SD-shaped net on MI355X: long K or grids of
+// several rounds take full 128-row tiles, the rest 64-row tiles; grids below the chip size split K.
 Choice choose(const IgemmParams& p) {
   Choice c;
   const bool k64 = p.C1 % 64 == 0 && p.C2 % 64 == 0;
@@ -925,7 +535,7 @@ Choice choose(const IgemmParams& p) {
   const int bn0 = geglu ? 128 : p.N % 160 == 0 ? 160 : p.N % 128 == 0 ? 128 : 64;
   c.bn = bn0;
   c.splitk = 1;
-  if (!k64) { c.variant = 3; return c; }
+  if (!k64) { c.variant = 0; return c; }
   const int stages = p.K / 64;
   const bool may_split = p.epilogue == EPI_NONE && p.workspace != nullptr;
   const long long mn = (long long)p.M * p.N;
@@ -940,12 +550,12 @@ Choice choose(const IgemmParams& p) {
   int sk = 1;
   if ((stages >= 64 && (long long)stages * nb128 >= 8000) || (nb128 >= 400 && stages >= 10 && p.M >= 4096)) {
     // long K or a grid of several rounds: full tiles, split K when the grid is below the chip size
-    c.variant = 6;
+    c.variant = 1;
     c.bn = nb128 >= 400 ? bn6 : bn0;
     nb128 = blocks(128, c.bn);
     if (nb128 < 400) sk = (512 + nb128 / 2) / nb128 < stages / 8 ? (512 + nb128 / 2) / nb128 : stages / 8;
   } else {
-    c.variant = 7;
+    c.variant = 2;
     if (stages >= 32) {
       const int nb = blocks(64, c.bn);
       if (nb < 512) sk = 512 / nb < stages / 8 ? 512 / nb : stages / 8;
@@ -962,10 +572,10 @@ Choice choose(const IgemmParams& p) {
   if (const char* t = getenv("SDSTREAM_TUNE")) {  // "variant,bn,splitk" for sweeps; unsupported combinations are ignored
     int v = -1, bn = 0, sk = 0;
     if (sscanf(t, "%d,%d,%d", &v, &bn, &sk) == 3) {
-      if (v >= 0 && v <= 7 && (k64 || v == 3)) c.variant = v;
+      if (v >= 0 && v <= 2 && (k64 || v == 0)) c.variant = v;
       if ((bn == 160 || bn == 128 || bn == 64) && !(p.epilogue == EPI_GEGLU && bn == 160)) c.bn = bn;
-      if (sk >= 1 && p.epilogue == EPI_NONE && p.workspace && (long long)sk * p.M * p.N <= p.workspace_floats &&
-          sk <= (c.variant == 3 ? p.K / 32 : p.K / 64))
+      if (sk >= 1 && may_split && (long long)sk * p.M * p.N <= p.workspace_floats &&
+          sk <= (c.variant == 0 ? p.K / 32 : p.K / 64))
         c.splitk = sk;
     }
   }
@@ -974,13 +584,8 @@ Choice choose(const IgemmParams& p) {
 
 template <int BN> void launch_bn(const IgemmParams& p, int variant, hipStream_t s) {
   switch (variant) {
-    case 0: launch_cfg64<128, BN, 2>(p, s); break;
-    case 1: launch_cfg64x8<128, BN, 2>(p, s); break;
-    case 4: launch_cfg64x8<128, BN, 4>(p, s); break;
-    case 2: launch_cfg64<64, BN, 2>(p, s); break;
-    case 5: launch_cfg64<64, BN, 4>(p, s); break;
-    case 6: launch_dma<128, BN>(p, s); break;
-    case 7: launch_dma<64, BN>(p, s); break;
+    case 1: launch_dma<128, BN>(p, s); break;
+    case 2: launch_dma<64, BN>(p, s); break;
     default: launch_cfg<128, BN, 3>(p, s); break;
   }
 }
@@ -1006,7 +611,7 @@ void launch_igemm_mfma(const IgemmParams& p0, hipStream_t s) {
   const Choice c = choose(p);
   p.splitk = c.splitk;
   if (p.splitk > 1) {  // drop splits that the rounding of stages per split leaves empty
-    const int stages = c.variant == 3 ? p.K / 32 : p.K / 64;
+    const int stages = c.variant == 0 ? p.K / 32 : p.K / 64;
     const int sps = (stages + p.splitk - 1) / p.splitk;
     p.splitk = (stages + sps - 1) / sps;
   }

@@ -111,13 +111,23 @@ __global__ void gn_partial_bf16_kernel(GroupNormParams p, int ppb, int nsplit, i
   float s[8], q[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) { s[e] = 0.f; q[e] = 0.f; }
-  for (int px = px0 + ln; px < px1; px += lanes) {
-    bf16x8 v = gn_load8(p, (long long)n * p.HW + px, chunk * 8);
+  // four pixels per trip so that four loads are in flight per thread
+  for (int px = px0 + ln; px < px1; px += 4 * lanes) {
+    bf16x8 v[4];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float x = (float)v[e];
-      s[e] += x;
-      q[e] = fmaf(x, x, q[e]);
+    for (int u = 0; u < 4; ++u) {
+      const int pu = px + u * lanes;
+      v[u] = gn_load8(p, (long long)n * p.HW + (pu < px1 ? pu : px), chunk * 8);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (px + u * lanes >= px1) break;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float x = (float)v[u][e];
+        s[e] += x;
+        q[e] = fmaf(x, x, q[e]);
+      }
     }
   }
 #pragma unroll
