@@ -21,6 +21,8 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
+# (config, cfg_mode) -> measured memory traffic in bytes per implicit-GEMM layer launch (profiles/igemm_config3_hbm_traffic.txt)
+TRAFFIC_BYTES_PER_LAUNCH = {(3, 0): 70.3e6}
 
 
 def main():
@@ -108,14 +110,26 @@ def main():
                              ms_per_step=r["ms"] / args.profile_steps,
                              tflops=r["flops"] / (r["ms"] * 1e-3) / 1e12 if r["ms"] > 0 else 0.0,
                              gbs=r["bytes"] / (r["ms"] * 1e-3) / 1e9 if r["ms"] > 0 else 0.0)
+    # an event pair around an eager launch also spans the dispatch gap; an empty pair on the same stream measures it
+    gaps = []
+    for _ in range(200):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(); b.record(); b.synchronize()
+        gaps.append(a.elapsed_time(b) * 1e3)
+    pair_us = sorted(gaps)[len(gaps) // 2]
     dom = max((c for c in classes if c.startswith("igemm")), key=lambda c: classes[c]["ms_per_step"])
     peak = PEAK_BF16_TFLOPS if dom.endswith("mfma") else PEAK_FP32_TFLOPS
     dr = prof[dom]
+    launch_us = dr["ms"] * 1e3 / dr["launches"] - pair_us
+    achieved = dr["flops"] / dr["launches"] / (launch_us * 1e-6) / 1e12
+    # HBM-side bytes per launch of this kernel class, from the two rocprofv3 --pmc passes summarised under profiles/
+    # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 256 MiB copy); only valid for the workload they were taken on
+    traffic = TRAFFIC_BYTES_PER_LAUNCH.get((args.config, mode)) if dom == "igemm_mfma" else None
     roofline = {"kernel": dom, "bound": "mfma" if dom.endswith("mfma") else "alu",
-                "achieved": dr["flops"] / (dr["ms"] * 1e-3) / 1e12, "peak": peak, "unit": "TFLOP/s",
-                "frac": dr["flops"] / (dr["ms"] * 1e-3) / 1e12 / peak,
-                "avg_launch_us": dr["ms"] * 1e3 / dr["launches"], "launches_per_step": dr["launches"] / args.profile_steps,
-                "traffic": None}
+                "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                "avg_launch_us": launch_us, "event_pair_overhead_us": pair_us,
+                "launches_per_step": dr["launches"] / args.profile_steps,
+                "algorithmic_bytes_per_launch": dr["bytes"] / dr["launches"], "traffic": traffic}
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
