@@ -102,8 +102,13 @@ __device__ __forceinline__ bf16x8 gn_load8(const GroupNormParams& p, long long p
   return *(const bf16x8*)src;
 }
 
-__global__ void gn_partial_bf16_kernel(GroupNormParams p, int ppb, int nsplit, int chunks, int lanes) {
-  extern __shared__ float sm[];  // [lanes][C][2]
+// Both passes are latency chains, not streams (their time barely changes between 1 and 4 samples), so they are
+// built to be short: blocks of up to 1024 threads so that a thread touches 2-4 pixels with all its loads in
+// flight at once, and reductions in three parallel steps (pixel lanes -> channel totals -> 8 threads per group
+// with shuffles) instead of one thread per group walking LDS.
+__global__ __launch_bounds__(1024) void gn_partial_bf16_kernel(GroupNormParams p, int ppb, int nsplit, int chunks,
+                                                               int lanes) {
+  extern __shared__ float sm[];  // [lanes][C][2] per-lane sums, then [C][2] channel totals
   const int C = p.C1 + p.C2, cg = C / p.groups;
   const int n = blockIdx.x / nsplit, sp = blockIdx.x - n * nsplit;
   const int chunk = threadIdx.x % chunks, ln = threadIdx.x / chunks;
@@ -136,53 +141,70 @@ __global__ void gn_partial_bf16_kernel(GroupNormParams p, int ppb, int nsplit, i
     sm[(ln * C + chunk * 8 + e) * 2 + 1] = q[e];
   }
   __syncthreads();
-  for (int g = threadIdx.x; g < p.groups; g += blockDim.x) {
+  float* tot = sm + (size_t)lanes * C * 2;
+  for (int c = threadIdx.x; c < C; c += blockDim.x) {
     float ss = 0.f, qq = 0.f;
-    for (int l = 0; l < lanes; ++l)
-      for (int c = g * cg; c < (g + 1) * cg; ++c) {
-        ss += sm[(l * C + c) * 2];
-        qq += sm[(l * C + c) * 2 + 1];
-      }
-    float* dst = p.stats + (((long long)n * nsplit + sp) * p.groups + g) * 2;
-    dst[0] = ss;
-    dst[1] = qq;
+#pragma unroll 8
+    for (int l = 0; l < lanes; ++l) {
+      ss += sm[(l * C + c) * 2];
+      qq += sm[(l * C + c) * 2 + 1];
+    }
+    tot[c * 2] = ss;
+    tot[c * 2 + 1] = qq;
+  }
+  __syncthreads();
+  // blockDim is a multiple of 8 (launcher), so the 8 threads of a group are always in one wave and one trip
+  for (int idx = threadIdx.x; idx < p.groups * 8; idx += blockDim.x) {
+    const int g = idx >> 3, part = idx & 7;
+    float ss = 0.f, qq = 0.f;
+    for (int c = g * cg + part; c < (g + 1) * cg; c += 8) {
+      ss += tot[c * 2];
+      qq += tot[c * 2 + 1];
+    }
+#pragma unroll
+    for (int o = 1; o < 8; o <<= 1) {
+      ss += __shfl_xor(ss, o);
+      qq += __shfl_xor(qq, o);
+    }
+    if (part == 0) {
+      float* dst = p.stats + (((long long)n * nsplit + sp) * p.groups + g) * 2;
+      dst[0] = ss;
+      dst[1] = qq;
+    }
   }
 }
 
 // Pass 2: every block first folds the pixel-split partials of its sample into mean / rstd per group (in double,
 // fixed order, so all blocks of a sample agree bit for bit), then normalises its pixels.  `nsplit_p` is the split
-// count of pass 1 (at most 64, so the fold is a few loads per thread).
-__global__ void gn_apply_bf16_kernel(GroupNormParams p, int ppb, int nsplit, int chunks, int lanes, int nsplit_p) {
-  extern __shared__ double smd[];                 // [J][groups][2] partial folds, then [groups][2] floats: mean, rstd
+// count of pass 1 (at most 64: 8 threads per group take up to 8 partials each).
+__global__ __launch_bounds__(1024) void gn_apply_bf16_kernel(GroupNormParams p, int ppb, int nsplit, int chunks,
+                                                             int lanes, int nsplit_p) {
+  extern __shared__ float sm[];  // [groups][2]: mean, rstd
   const int C = p.C1 + p.C2, cg = C / p.groups;
   const int n = blockIdx.x / nsplit, sp = blockIdx.x - n * nsplit;
   const int chunk = threadIdx.x % chunks, ln = threadIdx.x / chunks;
-  const int J = 8;
-  for (int idx = threadIdx.x; idx < J * p.groups; idx += blockDim.x) {
-    const int j = idx / p.groups, g = idx - j * p.groups;
+  for (int idx = threadIdx.x; idx < p.groups * 8; idx += blockDim.x) {
+    const int g = idx >> 3, part = idx & 7;
     double ss = 0.0, qq = 0.0;
-    for (int k = j; k < nsplit_p; k += J) {
+#pragma unroll 8
+    for (int k = part; k < nsplit_p; k += 8) {
       const float* src = p.stats + (((long long)n * nsplit_p + k) * p.groups + g) * 2;
       ss += src[0];
       qq += src[1];
     }
-    smd[idx * 2] = ss;
-    smd[idx * 2 + 1] = qq;
-  }
-  __syncthreads();
-  float* sm = (float*)(smd + J * p.groups * 2);
-  for (int g = threadIdx.x; g < p.groups; g += blockDim.x) {
-    double ss = 0.0, qq = 0.0;
-    for (int j = 0; j < J; ++j) {
-      ss += smd[(j * p.groups + g) * 2];
-      qq += smd[(j * p.groups + g) * 2 + 1];
+#pragma unroll
+    for (int o = 1; o < 8; o <<= 1) {
+      ss += __shfl_xor(ss, o);
+      qq += __shfl_xor(qq, o);
     }
-    const double cnt = (double)p.HW * cg;
-    const double mean = ss / cnt;
-    double var = qq / cnt - mean * mean;
-    if (var < 0) var = 0;
-    sm[g * 2] = (float)mean;
-    sm[g * 2 + 1] = (float)(1.0 / sqrt(var + (double)p.eps));
+    if (part == 0) {
+      const double cnt = (double)p.HW * cg;
+      const double mean = ss / cnt;
+      double var = qq / cnt - mean * mean;
+      if (var < 0) var = 0;
+      sm[g * 2] = (float)mean;
+      sm[g * 2 + 1] = (float)(1.0 / sqrt(var + (double)p.eps));
+    }
   }
   __syncthreads();
   float sc[8], sh[8];
@@ -195,42 +217,63 @@ __global__ void gn_apply_bf16_kernel(GroupNormParams p, int ppb, int nsplit, int
   }
   const int px0 = sp * ppb, px1 = min(p.HW, px0 + ppb);
   bf16_t* out = (bf16_t*)p.out;
-  for (int px = px0 + ln; px < px1; px += lanes) {
-    const long long pix = (long long)n * p.HW + px;
-    bf16x8 v = gn_load8(p, pix, chunk * 8), o;
+  for (int px = px0 + ln; px < px1; px += 4 * lanes) {
+    bf16x8 v[4];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float y = fmaf((float)v[e], sc[e], sh[e]);
-      if (p.silu) y = y / (1.0f + __expf(-y));
-      o[e] = (bf16_t)y;
+    for (int u = 0; u < 4; ++u) {
+      const int pu = px + u * lanes;
+      v[u] = gn_load8(p, (long long)n * p.HW + (pu < px1 ? pu : px), chunk * 8);
     }
-    *(bf16x8*)(out + pix * C + chunk * 8) = o;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int pu = px + u * lanes;
+      if (pu >= px1) break;
+      bf16x8 o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float y = fmaf((float)v[u][e], sc[e], sh[e]);
+        if (p.silu) y = y / (1.0f + __expf(-y));
+        o[e] = (bf16_t)y;
+      }
+      *(bf16x8*)(out + ((long long)n * p.HW + pu) * C + chunk * 8) = o;
+    }
   }
+}
+
+// thread geometry of the fast path: `chunks` 16-byte chunks per pixel row x `lanes` pixels, a multiple of 8 threads
+int gn_lanes(int chunks) {
+  int lanes = 1024 / chunks;
+  if (lanes > 32) lanes = 32;
+  if (chunks % 8 != 0) lanes &= ~7;
+  return lanes;
 }
 
 bool gn_fast_ok(const GroupNormParams& p) {
   const int C = p.C1 + p.C2;
-  return p.C1 % 8 == 0 && p.C2 % 8 == 0 && C / 8 <= 1024;
+  return p.C1 % 8 == 0 && p.C2 % 8 == 0 && C / 8 <= 1024 && gn_lanes(C / 8) >= 1 &&
+         ((size_t)gn_lanes(C / 8) + 1) * C * 2 * sizeof(float) <= 160 * 1024;
 }
 
 void launch_gn_fast(const GroupNormParams& p, hipStream_t s) {
   const int C = p.C1 + p.C2, chunks = C / 8;
-  const int lanes = chunks >= 256 ? 1 : 256 / chunks;
+  const int lanes = gn_lanes(chunks);
   const int threads = chunks * lanes;
-  // pass 1: at most 64 pixel splits per sample (one block per compute unit at 4 samples)
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipFuncSetAttribute((const void*)gn_partial_bf16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    attr_set = true;
+  }
+  // pass 1: at most 64 pixel splits per sample, at most 4 pixels per thread
   int ppb_p = (p.HW + 63) / 64;
-  if (ppb_p < 2 * lanes) ppb_p = 2 * lanes;
+  if (ppb_p < lanes) ppb_p = lanes;
   const int nsplit_p = (p.HW + ppb_p - 1) / ppb_p;
   hipLaunchKernelGGL(gn_partial_bf16_kernel, dim3(p.samples * nsplit_p), dim3(threads),
-                     (size_t)lanes * C * 2 * sizeof(float), s, p, ppb_p, nsplit_p, chunks, lanes);
-  // pass 2: ~1024 blocks
-  long long want = ((long long)p.HW * p.samples + 1023) / 1024;
-  int ppb = (int)(want < 2 * lanes ? 2 * lanes : want);
-  if (ppb > 64) ppb = 64;
+                     ((size_t)lanes + 1) * C * 2 * sizeof(float), s, p, ppb_p, nsplit_p, chunks, lanes);
+  // pass 2: two pixels per thread
+  const int ppb = 2 * lanes;
   const int nsplit = (p.HW + ppb - 1) / ppb;
-  hipLaunchKernelGGL(gn_apply_bf16_kernel, dim3(p.samples * nsplit), dim3(threads),
-                     (size_t)8 * p.groups * 2 * sizeof(double) + (size_t)p.groups * 2 * sizeof(float), s, p, ppb, nsplit,
-                     chunks, lanes, nsplit_p);
+  hipLaunchKernelGGL(gn_apply_bf16_kernel, dim3(p.samples * nsplit), dim3(threads), (size_t)p.groups * 2 * sizeof(float),
+                     s, p, ppb, nsplit, chunks, lanes, nsplit_p);
 }
 
 }  // namespace
