@@ -70,6 +70,103 @@ __global__ __launch_bounds__(256) void conv_out_kernel(const T* __restrict__ x, 
   }
 }
 
+// Fast forms for the usual case of 4 latent channels and bf16 activations.
+// conv_in: a thread owns one output channel with its 36 weights in registers (read straight from OIHW: 144
+// contiguous bytes per thread); the block's 32 pixel patches sit in LDS and are read as broadcasts.
+constexpr int CIF_PIX = 32;
+__global__ __launch_bounds__(1024) void conv_in4_bf16_kernel(const float* __restrict__ x, const float* __restrict__ w,
+                                                             const float* __restrict__ b, bf16_t* __restrict__ out, int N,
+                                                             int H, int W, int C0) {
+  __shared__ __attribute__((aligned(16))) float patch[CIF_PIX * 36];
+  const long long total_pix = (long long)N * H * W;
+  const long long pix0 = (long long)blockIdx.x * CIF_PIX;
+  for (int i = threadIdx.x; i < CIF_PIX * 36; i += blockDim.x) {
+    const int p = i / 36, k = i - p * 36;
+    const long long pix = pix0 + p;
+    float v = 0.f;
+    if (pix < total_pix) {
+      const int xx = (int)(pix % W), yy = (int)((pix / W) % H), n = (int)(pix / ((long long)W * H));
+      const int ci = k / 9, t = k - ci * 9;
+      const int iy = yy + t / 3 - 1, ix = xx + t % 3 - 1;
+      if (iy >= 0 && iy < H && ix >= 0 && ix < W) v = x[(((long long)n * 4 + ci) * H + iy) * W + ix];
+    }
+    patch[i] = v;
+  }
+  __syncthreads();
+  const int co = threadIdx.x;
+  if (co >= C0) return;
+  float4 wv[9];
+#pragma unroll
+  for (int j = 0; j < 9; ++j) wv[j] = ((const float4*)(w + (long long)co * 36))[j];
+  const float bias = b[co];
+  const int npix = (int)(total_pix - pix0 < CIF_PIX ? total_pix - pix0 : CIF_PIX);
+  for (int p = 0; p < npix; ++p) {
+    const float4* pp = (const float4*)(patch + p * 36);
+    float acc = bias;
+#pragma unroll
+    for (int j = 0; j < 9; ++j) {
+      const float4 v = pp[j];
+      acc = fmaf(wv[j].x, v.x, acc);
+      acc = fmaf(wv[j].y, v.y, acc);
+      acc = fmaf(wv[j].z, v.z, acc);
+      acc = fmaf(wv[j].w, v.w, acc);
+    }
+    out[(pix0 + p) * C0 + co] = (bf16_t)acc;
+  }
+}
+
+// conv_out: a wave owns a pixel at a time; lane l takes channels 8l..8l+7 of all nine taps (nine 16-byte loads in
+// flight), the 4 x 9 x C0 weights sit in LDS as bf16, and four wave reductions finish the pixel.
+constexpr int COF_PIX = 16;
+__global__ __launch_bounds__(256) void conv_out4_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ w,
+                                                             const float* __restrict__ b, float* __restrict__ out, int N,
+                                                             int H, int W, int C0) {
+  typedef __attribute__((ext_vector_type(8))) __bf16 v8;
+  extern __shared__ __attribute__((aligned(16))) unsigned char wl[];  // [4][9][C0] bf16
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int chunks = C0 >> 3;
+  for (int i = threadIdx.x; i < 36 * chunks; i += 256) ((v8*)wl)[i] = ((const v8*)w)[i];
+  __syncthreads();
+  const long long total_pix = (long long)N * H * W;
+  for (int pp = wave; pp < COF_PIX; pp += 4) {
+    const long long pix = (long long)blockIdx.x * COF_PIX + pp;
+    if (pix >= total_pix) break;
+    const int xx = (int)(pix % W), yy = (int)((pix / W) % H), n = (int)(pix / ((long long)W * H));
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int c = lane; c < chunks; c += 64) {
+      v8 xv[9];
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap) {
+        const int iy = yy + tap / 3 - 1, ix = xx + tap % 3 - 1;
+        const bool ok = iy >= 0 && iy < H && ix >= 0 && ix < W;
+        const long long src = (((long long)n * H + (ok ? iy : yy)) * W + (ok ? ix : xx)) * C0;
+        xv[tap] = *(const v8*)(x + src + c * 8);
+        if (!ok) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) xv[tap][e] = (bf16_t)0.f;
+        }
+      }
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+        for (int co = 0; co < 4; ++co) {
+          const v8 wv = ((const v8*)wl)[(co * 9 + tap) * chunks + c];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[co] = fmaf((float)xv[tap][e], (float)wv[e], acc[co]);
+        }
+    }
+#pragma unroll
+    for (int co = 0; co < 4; ++co) {
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) acc[co] += __shfl_xor(acc[co], o);
+    }
+    if (lane < 4) {
+      const float v = lane == 0 ? acc[0] : lane == 1 ? acc[1] : lane == 2 ? acc[2] : acc[3];
+      out[(((long long)n * 4 + lane) * H + yy) * W + xx] = v + b[lane];
+    }
+  }
+}
+
 // ---------------------------------------------------------------- time embedding
 __global__ void time_embedding_kernel(const int* t, float* out, int rows, int C0) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -262,6 +359,12 @@ template <typename T>
 void launch_conv_in(const float* x, const float* w, const float* b, void* out, int N, int Cin, int H, int W, int C0,
                     hipStream_t s) {
   long long pix = (long long)N * H * W;
+  if (sizeof(T) == 2 && Cin == 4 && C0 <= 1024) {
+    const int threads = (C0 + 63) / 64 * 64;
+    hipLaunchKernelGGL(conv_in4_bf16_kernel, dim3((unsigned)((pix + CIF_PIX - 1) / CIF_PIX)), dim3(threads), 0, s, x, w,
+                       b, (bf16_t*)out, N, H, W, C0);
+    return;
+  }
   size_t lds = (size_t)(Cin * 9 * C0 + CI_PIX * Cin * 9) * sizeof(float);
   hipLaunchKernelGGL(conv_in_kernel<T>, dim3((unsigned)((pix + CI_PIX - 1) / CI_PIX)), dim3(256), lds, s, x, w, b,
                      (T*)out, N, Cin, H, W, C0);
@@ -273,6 +376,11 @@ template <typename T>
 void launch_conv_out(const void* x, const void* w, const float* b, float* out, int N, int Cout, int H, int W, int C0,
                      hipStream_t s) {
   long long pix = (long long)N * H * W;
+  if (sizeof(T) == 2 && Cout == 4 && C0 % 8 == 0 && (size_t)36 * C0 * 2 <= 64 * 1024) {
+    hipLaunchKernelGGL(conv_out4_bf16_kernel, dim3((unsigned)((pix + COF_PIX - 1) / COF_PIX)), dim3(256),
+                       (size_t)36 * C0 * 2, s, (const bf16_t*)x, (const bf16_t*)w, b, out, N, H, W, C0);
+    return;
+  }
   hipLaunchKernelGGL(conv_out_kernel<T>, dim3((unsigned)((pix + 3) / 4)), dim3(256), 0, s, (const T*)x, (const T*)w, b,
                      out, N, Cout, H, W, C0);
 }
