@@ -20,6 +20,14 @@ which is what makes Stream Batch exact, Sec. 3.1).
   up path        : per level, deepest first: (layers+1) x (concat skip -> ResBlock [, Transformer]);
                    nearest 2x + conv3x3 except at level 0
   out            : GN -> SiLU -> conv3x3
+
+Stream Batch cross-frame attention (Sec. 3.2, the two K_Batch / V_Batch equations and the Attn equation
+after them): when it is on, the rows handed to one call are one stream batch; every self-attention then
+uses, for each row's queries, the keys and values of ALL rows of the call concatenated along the token
+axis (softmax over n x HW keys, scale 1/sqrt(d) unchanged).  Cross-attention to the prompt, and everything
+else, still treats rows independently.  The paper does not say which rows form a batch under guidance;
+the reading here is "the rows of one call": the positive-prompt rows of a stream, or its negative-prompt
+rows, each among themselves, and the single onetime-negative row alone.
 """
 from __future__ import annotations
 
@@ -223,76 +231,103 @@ def res_block(P, p: str, x, temb, groups: int):
     return x + h
 
 
+def transformer_rows(P, p: str, xs, ctx, heads: int, groups: int, cross_frame: bool):
+    """The transformer block on a list of rows.  Only the self-attention can couple rows (cross_frame)."""
+    c, hh, ww = xs[0].shape
+    hs = []
+    for x in xs:
+        h = group_norm(x, groups, P[p + ".norm.g"], P[p + ".norm.b"], 1e-6)
+        h = h.reshape(c, hh * ww).T                               # tokens [HW, C]
+        hs.append(_linear(h, P[p + ".proj_in.w"], P[p + ".proj_in.b"]))
+    ns = [layer_norm(h, P[p + ".ln1.g"], P[p + ".ln1.b"]) for h in hs]
+    qs = [_linear(n, P[p + ".attn1.q.w"]) for n in ns]
+    ks = [_linear(n, P[p + ".attn1.k.w"]) for n in ns]
+    vs = [_linear(n, P[p + ".attn1.v.w"]) for n in ns]
+    if cross_frame:
+        k_batch, v_batch = torch.cat(ks, dim=0), torch.cat(vs, dim=0)     # K_Batch, V_Batch of Sec. 3.2
+        att = [attention(q, k_batch, v_batch, heads) for q in qs]
+    else:
+        att = [attention(q, k, v, heads) for q, k, v in zip(qs, ks, vs)]
+    out = []
+    for x, h, a in zip(xs, hs, att):
+        h = h + _linear(a, P[p + ".attn1.o.w"], P[p + ".attn1.o.b"])
+        n = layer_norm(h, P[p + ".ln2.g"], P[p + ".ln2.b"])
+        a = attention(_linear(n, P[p + ".attn2.q.w"]), _linear(ctx, P[p + ".attn2.k.w"]),
+                      _linear(ctx, P[p + ".attn2.v.w"]), heads)
+        h = h + _linear(a, P[p + ".attn2.o.w"], P[p + ".attn2.o.b"])
+        n = layer_norm(h, P[p + ".ln3.g"], P[p + ".ln3.b"])
+        u = _linear(n, P[p + ".ff.in.w"], P[p + ".ff.in.b"])
+        inner = u.shape[1] // 2
+        u = u[:, :inner] * gelu_erf(u[:, inner:])
+        h = h + _linear(u, P[p + ".ff.out.w"], P[p + ".ff.out.b"])
+        h = _linear(h, P[p + ".proj_out.w"], P[p + ".proj_out.b"])
+        out.append(x + h.T.reshape(c, hh, ww))
+    return out
+
+
 def transformer(P, p: str, x, ctx, heads: int, groups: int):
-    c, hh, ww = x.shape
-    h = group_norm(x, groups, P[p + ".norm.g"], P[p + ".norm.b"], 1e-6)
-    h = h.reshape(c, hh * ww).T                                   # tokens [HW, C]
-    h = _linear(h, P[p + ".proj_in.w"], P[p + ".proj_in.b"])
-    n = layer_norm(h, P[p + ".ln1.g"], P[p + ".ln1.b"])
-    a = attention(_linear(n, P[p + ".attn1.q.w"]), _linear(n, P[p + ".attn1.k.w"]),
-                  _linear(n, P[p + ".attn1.v.w"]), heads)
-    h = h + _linear(a, P[p + ".attn1.o.w"], P[p + ".attn1.o.b"])
-    n = layer_norm(h, P[p + ".ln2.g"], P[p + ".ln2.b"])
-    a = attention(_linear(n, P[p + ".attn2.q.w"]), _linear(ctx, P[p + ".attn2.k.w"]),
-                  _linear(ctx, P[p + ".attn2.v.w"]), heads)
-    h = h + _linear(a, P[p + ".attn2.o.w"], P[p + ".attn2.o.b"])
-    n = layer_norm(h, P[p + ".ln3.g"], P[p + ".ln3.b"])
-    u = _linear(n, P[p + ".ff.in.w"], P[p + ".ff.in.b"])
-    inner = u.shape[1] // 2
-    u = u[:, :inner] * gelu_erf(u[:, inner:])
-    h = h + _linear(u, P[p + ".ff.out.w"], P[p + ".ff.out.b"])
-    h = _linear(h, P[p + ".proj_out.w"], P[p + ".proj_out.b"])
-    return x + h.T.reshape(c, hh, ww)
+    return transformer_rows(P, p, [x], ctx, heads, groups, False)[0]
+
+
+def unet_rows(s: UNetShape, P: Dict[str, torch.Tensor], xs, ts: Sequence[int], ctx: torch.Tensor,
+              cross_frame: bool = False) -> List[torch.Tensor]:
+    """Rows xs[i] [C_in,H,W] at integer timesteps ts[i], ctx [L,D] shared -> predicted noise per row.
+    Rows interact only through the self-attention, and only when cross_frame is set."""
+    ch = s.block_channels
+    nl = len(ch)
+    g = s.norm_groups
+    R = range(len(xs))
+    ctx = ctx.to(DT)
+    tembs = []
+    for t in ts:
+        e = time_embedding(int(t), ch[0])
+        tembs.append(_linear(silu(_linear(e, P["time.lin1.w"], P["time.lin1.b"])), P["time.lin2.w"], P["time.lin2.b"]))
+    hs = [conv2d(x.to(DT), P["conv_in.w"], P["conv_in.b"]) for x in xs]
+    skips = [hs]
+    for l in range(nl):
+        for j in range(s.layers_per_block):
+            hs = [res_block(P, f"down.{l}.res.{j}", hs[r], tembs[r], g) for r in R]
+            if s.attn_levels[l]:
+                hs = transformer_rows(P, f"down.{l}.attn.{j}", hs, ctx, s.heads(ch[l]), g, cross_frame)
+            skips.append(hs)
+        if l != nl - 1:
+            hs = [conv2d(h, P[f"down.{l}.downsample.w"], P[f"down.{l}.downsample.b"], stride=2) for h in hs]
+            skips.append(hs)
+    hs = [res_block(P, "mid.res.0", hs[r], tembs[r], g) for r in R]
+    if s.mid_attention:
+        hs = transformer_rows(P, "mid.attn", hs, ctx, s.heads(ch[-1]), g, cross_frame)
+    hs = [res_block(P, "mid.res.1", hs[r], tembs[r], g) for r in R]
+    for l in reversed(range(nl)):
+        for j in range(s.layers_per_block + 1):
+            sk = skips.pop()
+            hs = [res_block(P, f"up.{l}.res.{j}", torch.cat([hs[r], sk[r]], dim=0), tembs[r], g) for r in R]
+            if s.attn_levels[l]:
+                hs = transformer_rows(P, f"up.{l}.attn.{j}", hs, ctx, s.heads(ch[l]), g, cross_frame)
+        if l != 0:
+            hs = [conv2d(upsample_nearest2(h), P[f"up.{l}.upsample.w"], P[f"up.{l}.upsample.b"]) for h in hs]
+    assert not skips
+    hs = [silu(group_norm(h, g, P["out.norm.g"], P["out.norm.b"], 1e-5)) for h in hs]
+    return [conv2d(h, P["conv_out.w"], P["conv_out.b"]) for h in hs]
 
 
 def unet_single(s: UNetShape, P: Dict[str, torch.Tensor], x: torch.Tensor, t: int, ctx: torch.Tensor) -> torch.Tensor:
     """One sample: x [C_in,H,W], integer timestep t, ctx [L,D] -> predicted noise [C_in,H,W]."""
-    ch = s.block_channels
-    nl = len(ch)
-    g = s.norm_groups
-    x = x.to(DT)
-    ctx = ctx.to(DT)
-    temb = time_embedding(int(t), ch[0])
-    temb = _linear(silu(_linear(temb, P["time.lin1.w"], P["time.lin1.b"])), P["time.lin2.w"], P["time.lin2.b"])
-    h = conv2d(x, P["conv_in.w"], P["conv_in.b"])
-    skips = [h]
-    for l in range(nl):
-        for j in range(s.layers_per_block):
-            h = res_block(P, f"down.{l}.res.{j}", h, temb, g)
-            if s.attn_levels[l]:
-                h = transformer(P, f"down.{l}.attn.{j}", h, ctx, s.heads(ch[l]), g)
-            skips.append(h)
-        if l != nl - 1:
-            h = conv2d(h, P[f"down.{l}.downsample.w"], P[f"down.{l}.downsample.b"], stride=2)
-            skips.append(h)
-    h = res_block(P, "mid.res.0", h, temb, g)
-    if s.mid_attention:
-        h = transformer(P, "mid.attn", h, ctx, s.heads(ch[-1]), g)
-    h = res_block(P, "mid.res.1", h, temb, g)
-    for l in reversed(range(nl)):
-        for j in range(s.layers_per_block + 1):
-            h = res_block(P, f"up.{l}.res.{j}", torch.cat([h, skips.pop()], dim=0), temb, g)
-            if s.attn_levels[l]:
-                h = transformer(P, f"up.{l}.attn.{j}", h, ctx, s.heads(ch[l]), g)
-        if l != 0:
-            h = conv2d(upsample_nearest2(h), P[f"up.{l}.upsample.w"], P[f"up.{l}.upsample.b"])
-    assert not skips
-    h = silu(group_norm(h, g, P["out.norm.g"], P["out.norm.b"], 1e-5))
-    return conv2d(h, P["conv_out.w"], P["conv_out.b"])
+    return unet_rows(s, P, [x], [t], ctx, False)[0]
 
 
 class UNet:
-    """eps_theta with a call counter (the paper counts U-Net evaluations per frame, Sec. 3.3)."""
+    """eps_theta with a call counter (the paper counts U-Net evaluations per frame, Sec. 3.3).
+    cross_frame: the rows of one call form a stream batch for cross-frame attention (Sec. 3.2)."""
 
-    def __init__(self, shape: UNetShape, blob):
+    def __init__(self, shape: UNetShape, blob, cross_frame: bool = False):
         self.shape = shape
         self.P = unpack(shape, blob)
+        self.cross_frame = bool(cross_frame)
         self.evaluations = 0
 
     def __call__(self, x: torch.Tensor, t: Sequence[int], ctx: torch.Tensor) -> torch.Tensor:
         """x [N,C,H,W], t [N], ctx [L,D] shared by all rows -> eps [N,C,H,W]."""
-        out = []
-        for i in range(x.shape[0]):
-            out.append(unet_single(self.shape, self.P, x[i], int(t[i]), ctx))
-            self.evaluations += 1
-        return torch.stack(out)
+        self.evaluations += x.shape[0]
+        if self.cross_frame:
+            return torch.stack(unet_rows(self.shape, self.P, list(x), [int(v) for v in t], ctx, True))
+        return torch.stack([unet_single(self.shape, self.P, x[i], int(t[i]), ctx) for i in range(x.shape[0])])
