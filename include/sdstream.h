@@ -62,6 +62,10 @@ typedef struct {
   int32_t n_streams;                            /* S independent streams sharing weights, noise and prompt     */
   int32_t cfg_mode;                             /* SDSTREAM_CFG_*                                              */
   int32_t scheduler;                            /* 0: LCM re-noising with the cached noise; 1: DDIM (eta = 0)  */
+  int32_t cross_frame;                          /* 1: Stream Batch cross-frame attention (Sec. 3.2, K_Batch /  */
+                                                /*    V_Batch): every self-attention of a row uses the keys and */
+                                                /*    values of all n rows of its stream (and prompt branch);   */
+                                                /*    0: rows independent                                       */
 } sdstream_config;
 
 /* Creates an engine on the current HIP device and allocates all device state.  No weights yet. */

@@ -24,7 +24,7 @@ class Config(C.Structure):
                 ("head_dim", C.c_int32), ("mid_attention", C.c_int32), ("context_len", C.c_int32),
                 ("context_dim", C.c_int32), ("norm_groups", C.c_int32), ("latent_h", C.c_int32),
                 ("latent_w", C.c_int32), ("dtype", C.c_int32), ("n_denoise", C.c_int32), ("n_streams", C.c_int32),
-                ("cfg_mode", C.c_int32), ("scheduler", C.c_int32)]
+                ("cfg_mode", C.c_int32), ("scheduler", C.c_int32), ("cross_frame", C.c_int32)]
 
 
 class ProfileEntry(C.Structure):
@@ -82,7 +82,7 @@ def exported_symbols():
 
 
 def config_from_dict(unet: dict, latent, dtype: str, n_denoise: int, n_streams: int, cfg_mode: int,
-                     scheduler: int = 0) -> Config:
+                     scheduler: int = 0, cross_frame: int = 0) -> Config:
     c = Config()
     ch = list(unet["block_channels"])
     c.in_channels = unet["in_channels"]
@@ -98,6 +98,7 @@ def config_from_dict(unet: dict, latent, dtype: str, n_denoise: int, n_streams: 
     c.latent_h, c.latent_w = latent
     c.dtype = {"fp32": 0, "bf16": 1}[dtype]
     c.n_denoise, c.n_streams, c.cfg_mode, c.scheduler = n_denoise, n_streams, cfg_mode, scheduler
+    c.cross_frame = int(cross_frame)
     return c
 
 

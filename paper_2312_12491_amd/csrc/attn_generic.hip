@@ -23,6 +23,11 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(AttnParams p) {
   const T* V = (const T*)p.v;
   long long kvoff = p.kv_select ? (long long)p.kv_select[sample] * p.kv_select_stride
                                 : (long long)sample * p.kv_sample_stride;
+  int Skv = p.Skv;
+  if (p.kv_group > 1 && sample < p.kv_group_rows) {  // keys / values of the whole stream batch, in batch order
+    kvoff = (long long)(sample - sample % p.kv_group) * p.kv_sample_stride;
+    Skv = p.Skv * p.kv_group;
+  }
   const bool q_ok = qi < p.Sq;
 
   float q[DP], o[DP];
@@ -35,13 +40,13 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(AttnParams p) {
   }
   float mrun = -INFINITY, lrun = 0.f;
 
-  for (int j0 = 0; j0 < p.Skv; j0 += KT) {
+  for (int j0 = 0; j0 < Skv; j0 += KT) {
     __syncthreads();
     for (int i = tid; i < KT * p.d; i += 256) {
       int r = i / p.d, c = i - r * p.d;
       int j = j0 + r;
       float kv = 0.f, vv = 0.f;
-      if (j < p.Skv) {
+      if (j < Skv) {
         kv = to_f32<T>(K[kvoff + (long long)j * p.ldk + c0 + c]);
         vv = to_f32<T>(V[kvoff + (long long)j * p.ldv + c0 + c]);
       }
@@ -49,7 +54,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(AttnParams p) {
       Vs[r][c] = vv;
     }
     __syncthreads();
-    const int jn = min(KT, p.Skv - j0);
+    const int jn = min(KT, Skv - j0);
     for (int r = 0; r < jn; ++r) {
       float s = 0.f;
 #pragma unroll

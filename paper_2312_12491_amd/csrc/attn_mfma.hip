@@ -53,8 +53,13 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
   const bf16_t* Q = (const bf16_t*)p.q;
   const bf16_t* K = (const bf16_t*)p.k;
   const bf16_t* V = (const bf16_t*)p.v;
-  const long long kvoff = p.kv_select ? (long long)p.kv_select[sample] * p.kv_select_stride
-                                      : (long long)sample * p.kv_sample_stride;
+  long long kvoff = p.kv_select ? (long long)p.kv_select[sample] * p.kv_select_stride
+                                : (long long)sample * p.kv_sample_stride;
+  int Skv = p.Skv;
+  if (p.kv_group > 1 && sample < p.kv_group_rows) {  // keys / values of the whole stream batch, in batch order
+    kvoff = (long long)(sample - sample % p.kv_group) * p.kv_sample_stride;
+    Skv = p.Skv * p.kv_group;
+  }
   const int q0 = blockIdx.x * BQ + wave * (QT * 16);
 
   // zero both buffers once: padding columns / rows are never written again
@@ -96,7 +101,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
       uint4 v = make_uint4(0, 0, 0, 0);
       if (ch < nkchunks) {
         int r = ch / dchunks, c = ch - r * dchunks;
-        if (j0 + r < p.Skv) v = *(const uint4*)(K + kvoff + (long long)(j0 + r) * p.ldk + c0 + c * 8);
+        if (j0 + r < Skv) v = *(const uint4*)(K + kvoff + (long long)(j0 + r) * p.ldk + c0 + c * 8);
       }
       kreg[i] = v;
     }
@@ -104,7 +109,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
     for (int i = 0; i < VSLOTS; ++i) {
       int c = (tid >> 6) + 4 * i, r = tid & 63;
       uint4 v = make_uint4(0, 0, 0, 0);
-      if (c < dchunks && j0 + r < p.Skv) v = *(const uint4*)(V + kvoff + (long long)(j0 + r) * p.ldv + c0 + c * 8);
+      if (c < dchunks && j0 + r < Skv) v = *(const uint4*)(V + kvoff + (long long)(j0 + r) * p.ldv + c0 + c * 8);
       vreg[i] = v;
     }
   };
@@ -135,10 +140,10 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
   store_tiles(0);
   __syncthreads();
   int buf = 0;
-  for (int j0 = 0; j0 < p.Skv; j0 += BKV, buf ^= 1) {
+  for (int j0 = 0; j0 < Skv; j0 += BKV, buf ^= 1) {
     const unsigned char* Ks = smem + buf * TILE;
     const unsigned char* Vs = Ks + KBYTES;
-    const bool more = j0 + BKV < p.Skv;
+    const bool more = j0 + BKV < Skv;
     if (more) load_tiles(j0 + BKV);  // in flight while this tile is multiplied
 
     // S^T tiles: rows = keys 16*kt + 4g + v, column = query li; every K fragment serves all QT query tiles
@@ -161,12 +166,12 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
       f32x4(&s)[4] = sacc[t];
-      if (j0 + BKV > p.Skv) {  // ragged last tile: keys past the end must not win the max or add to the sum
+      if (j0 + BKV > Skv) {  // ragged last tile: keys past the end must not win the max or add to the sum
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
           for (int v = 0; v < 4; ++v)
-            if (j0 + kt * 16 + g * 4 + v >= p.Skv) s[kt][v] = -3.0e38f;
+            if (j0 + kt * 16 + g * 4 + v >= Skv) s[kt][v] = -3.0e38f;
       }
       float mx = s[0][0];
 #pragma unroll

@@ -74,6 +74,9 @@ struct AttnParams {
   long long kv_sample_stride;   // elements between samples in k/v (0 with kv_select: cached prompt K/V)
   const int* kv_select;         // per sample: which cached context (0 positive, 1 negative) or null
   long long kv_select_stride;   // elements between cached contexts
+  int kv_group;                 // > 1: Stream Batch cross-frame attention (Sec. 3.2): samples [0, kv_group_rows) come in runs
+  int kv_group_rows;            //   of kv_group consecutive samples that attend to the keys / values of the whole run
+                                //   (k/v rows of consecutive samples must be contiguous: kv_sample_stride = Skv * ld)
   float scale;
 };
 

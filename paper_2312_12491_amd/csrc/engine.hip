@@ -383,7 +383,9 @@ struct Builder {
     op.mfma = e.use_mfma && attention_mfma_supported(p);
     op.cls = op.mfma ? PC_ATTN_MFMA : PC_ATTN_VALU;
     op.rows_per_sample = Sq;
-    op.flops_per_row = 4.0 * Sq * (double)Skv * d * heads;
+    // with cross-frame attention a self-attention row sees the keys of all n rows of its stream batch
+    const double kv_rows = (!cached && e.cfg.cross_frame && e.cfg.n_denoise > 1) ? e.cfg.n_denoise : 1;
+    op.flops_per_row = 4.0 * Sq * (double)Skv * kv_rows * d * heads;
     op.bytes_per_row = (2.0 * Sq * heads * d + (cached ? 0.0 : 2.0 * Skv * heads * d)) * e.elt;
     e.ops.push_back(op);
     return p.out;
@@ -692,6 +694,7 @@ int validate(const sdstream_config& c, std::string& why) {
   if (c.n_streams < 1 || c.n_streams > 64) BAD("n_streams %d out of range", c.n_streams);
   if (c.cfg_mode < 0 || c.cfg_mode > 3) BAD("cfg_mode %d", c.cfg_mode);
   if (c.scheduler < 0 || c.scheduler > 1) BAD("scheduler %d", c.scheduler);
+  if (c.cross_frame < 0 || c.cross_frame > 1) BAD("cross_frame %d", c.cross_frame);
   for (int l = 0; l < c.n_levels; ++l) {
     int ch = c.block_channels[l];
     if (ch < 1 || ch % c.norm_groups) BAD("block_channels[%d]=%d not a multiple of norm_groups", l, ch);
@@ -737,7 +740,7 @@ void reset_state(sdstream* h) {
 // ------------------------------------------------------------------------------------------------
 // launching
 // ------------------------------------------------------------------------------------------------
-void launch_op(sdstream* h, const Op& op0, int N, const int* kv_select, hipStream_t s) {
+void launch_op(sdstream* h, const Op& op0, int N, const int* kv_select, int xframe_rows, hipStream_t s) {
   const bool bf = h->cfg.dtype == 1;
   switch (op0.kind) {
     case OP_IGEMM: {
@@ -768,7 +771,13 @@ void launch_op(sdstream* h, const Op& op0, int N, const int* kv_select, hipStrea
     case OP_ATTN: {
       AttnParams p = op0.at;
       p.samples = N;
-      if (p.kv_select) p.kv_select = kv_select;
+      if (p.kv_select) {
+        p.kv_select = kv_select;
+      } else if (h->cfg.cross_frame && h->cfg.n_denoise > 1) {
+        // Sec. 3.2: the n rows of a stream batch attend to the keys and values of all of them
+        p.kv_group = h->cfg.n_denoise;
+        p.kv_group_rows = xframe_rows;
+      }
       if (op0.mfma) launch_attention_mfma(p, s);
       else if (bf) launch_attention_generic<bf16_t>(p, s);
       else launch_attention_generic<float>(p, s);
@@ -808,6 +817,11 @@ int prof_end(sdstream* h, hipStream_t s) {
 // the U-Net on `N` rows: x (fp32 NCHW, device) -> eps (fp32 NCHW, device)
 int run_unet(sdstream* h, const float* x, float* eps, int N, const int* kv_select, bool for_step, hipStream_t s) {
   const bool graph = h->graph_enabled && !h->profiling && for_step;
+  // rows that come in stream batches of n for cross-frame attention: in a step the positive-prompt rows (and, with
+  // full CFG, their negative-prompt copies; the onetime-negative rows stay alone); in a plain forward call every
+  // complete run of n rows
+  const int nd = h->cfg.n_denoise;
+  const int xframe_rows = for_step ? (h->cfg.cfg_mode == SDSTREAM_CFG_FULL ? 2 : 1) * h->cfg.n_streams * nd : N / nd * nd;
   // the first and last op read / write caller-visible buffers
   h->ops.front().cin = x;
   h->ops.back().cout_ = eps;
@@ -817,7 +831,7 @@ int run_unet(sdstream* h, const float* x, float* eps, int N, const int* kv_selec
     if (it == h->graphs.end()) {
       if (!h->cap_stream) HIP_TRY(h, hipStreamCreateWithFlags(&h->cap_stream, hipStreamNonBlocking));
       HIP_TRY(h, hipStreamBeginCapture(h->cap_stream, hipStreamCaptureModeThreadLocal));
-      for (const Op& op : h->ops) launch_op(h, op, N, kv_select, h->cap_stream);
+      for (const Op& op : h->ops) launch_op(h, op, N, kv_select, xframe_rows, h->cap_stream);
       hipGraph_t gph = nullptr;
       HIP_TRY(h, hipStreamEndCapture(h->cap_stream, &gph));
       hipGraphExec_t ex = nullptr;
@@ -834,7 +848,7 @@ int run_unet(sdstream* h, const float* x, float* eps, int N, const int* kv_selec
         int rc = prof_begin(h, op.cls, op.flops_per_row * N, op.bytes_per_row * N + op.bytes_fixed, s, (int)oi, N);
         if (rc) return rc;
       }
-      launch_op(h, op, N, kv_select, s);
+      launch_op(h, op, N, kv_select, xframe_rows, s);
       if (h->profiling) {
         int rc = prof_end(h, s);
         if (rc) return rc;

@@ -287,9 +287,11 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma_kernel(IgemmParams p, int m
 // fetches the row's 16-byte chunk j ^ ((r >> 1) & 7) and the fragment reads apply the same XOR, which spreads
 // the 16 rows of a fragment over all banks.  Rows outside the image or past M read the zero page instead.
 //
-// Pipeline (two LDS buffers, loads two stages ahead): a wave reads ALL fragments of stage s into registers,
-// the block synchronises, and the buffer is immediately refilled with stage s+2 while the MFMAs of stage s
-// run; stage s+1 is already in flight in the other buffer.  The loads are issued from inline assembly and
+// Pipeline (NBUF LDS buffers, loads NBUF stages ahead): a wave reads ALL fragments of stage s into registers,
+// the block synchronises, and the buffer is immediately refilled with stage s+NBUF while the MFMAs of stage s
+// run; stages s+1 .. s+NBUF-1 are already in flight in the other buffers.  NBUF = 2 keeps two blocks per compute
+// unit for the long-K layers; the short-K layers are one memory round trip per NBUF stages long, so they take
+// small tiles with NBUF = 4.  The loads are issued from inline assembly and
 // waited for with explicit vmcnt values (every wave issues the same number per stage), because the compiler
 // would otherwise drain all outstanding loads before each LDS read.
 // ---------------------------------------------------------------------------------------------------
@@ -307,7 +309,7 @@ __device__ __forceinline__ void lds_dma16(const void* gsrc, unsigned lds_base) {
       : "memory");
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int NBUF>
 __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mtiles, int ksteps_total,
                                                            int stages_per_split) {
   constexpr int WM = 2, WN = 2, NW = 4;
@@ -316,7 +318,7 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
   static_assert(BM % 32 == 0 && BN % 32 == 0, "loads must divide evenly over the waves");
   constexpr int NLOADS = NLA + NLB;
   constexpr int ABYTES = BM * 128, BBYTES = BN * 128, STAGE = ABYTES + BBYTES;
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // 2 stages of [A | B]
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // NBUF stages of [A | B]
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -355,21 +357,22 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
   }
   // B loads: load i of wave w is fragment f = i*NW + w of the stage: n-tile f/2, k-step f%2
   const int gnt_blk = n0 >> 4, ntiles_total = p.N >> 4;
-  unsigned boff[NLB];
-#pragma unroll
-  for (int i = 0; i < NLB; ++i) {
-    const int f = i * NW + wave;
-    int g = gnt_blk + (f >> 1);
-    if (g >= ntiles_total) g = ntiles_total - 1;  // columns past N are computed on valid data and dropped
-    boff[i] = ((unsigned)g * (unsigned)ksteps_total * 64u + (unsigned)((f & 1) * 64 + lane)) * 16u;
-  }
-
   const int total_stages = ksteps_total >> 1;
   const int stage0 = tile.split * stages_per_split;
   int nstages = total_stages - stage0;
   if (nstages > stages_per_split) nstages = stages_per_split;
   int l_stage = stage0;
   const int stage_last = total_stages - 1;
+  const char* bptr[NLB];   // this lane's 16 bytes of fragment i in the cursor's stage
+#pragma unroll
+  for (int i = 0; i < NLB; ++i) {
+    const int f = i * NW + wave;
+    int g = gnt_blk + (f >> 1);
+    if (g >= ntiles_total) g = ntiles_total - 1;  // columns past N are computed on valid data and dropped
+    bptr[i] = Wp + ((unsigned)g * (unsigned)ksteps_total * 64u + (unsigned)((f & 1) * 64 + lane)) * 16u +
+              (unsigned)min(l_stage, stage_last) * 2048u;
+  }
+
   int l_c, l_ky, l_kx;
   {
     int kk = stage0 * 64;
@@ -379,17 +382,22 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
     l_kx = tap - l_ky * p.ksize;
   }
 
-  // per-lane source pixel and validity of every A load for the cursor's tap; recomputed when the tap changes.
+  // Per-lane source address and validity of every A load for the cursor's position.  Inside a tap and a source
+  // the address just advances by 64 channels per stage; it is rebuilt when the tap or the source changes.
   // Past the last stage the tap index leaves the kernel window and every row reads the zero page.
-  unsigned lin[NLA];
+  const char* aptr[NLA];   // meaningless (and unused) where !okv
   bool okv[NLA];
   auto set_tap = [&]() {
     const bool live = l_ky < p.ksize;
+    const char* src;
+    int Cs, c = l_c;
+    if (c < p.C1) { src = s1; Cs = p.C1; } else { src = s2; Cs = p.C2; c -= p.C1; }
 #pragma unroll
     for (int i = 0; i < NLA; ++i) {
       const int iy = ld_y[i] + l_ky, ix = ld_x[i] + l_kx;
       okv[i] = live && ld_ok[i] && (unsigned)iy < (unsigned)Hs && (unsigned)ix < (unsigned)Wsz;
-      lin[i] = ld_pix0[i] + (unsigned)((iy >> ups) * p.Win + (ix >> ups));   // meaningless (and unused) if !okv
+      const unsigned lin = ld_pix0[i] + (unsigned)((iy >> ups) * p.Win + (ix >> ups));
+      aptr[i] = src + (lin * (unsigned)Cs + (unsigned)c + ld_ch[i]) * 2u;
     }
   };
   set_tap();
@@ -397,25 +405,25 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
   // issues the NLOADS loads of the cursor's stage into LDS buffer `buf` and advances the cursor
   auto issue = [&](int buf) {
     const unsigned sa = lds0 + buf * STAGE;
-    const char* src;
-    int Cs, c = l_c;
-    if (c < p.C1) { src = s1; Cs = p.C1; } else { src = s2; Cs = p.C2; c -= p.C1; }
 #pragma unroll
     for (int i = 0; i < NLA; ++i) {
-      // computed unconditionally (and made opaque) so that the choice below is a select, not a branch
-      unsigned off = (lin[i] * (unsigned)Cs + (unsigned)c + ld_ch[i]) * 2u;
-      asm volatile("" : "+v"(off));
-      const char* g = okv[i] ? src + off : zeros;
+      const char* g = okv[i] ? aptr[i] : zeros;
       lds_dma16(g, sa + (i * NW + wave) * 1024);
+      aptr[i] += 128;
     }
-    const unsigned kb = (unsigned)min(l_stage, stage_last) * 2048u;
+    const int bstep = l_stage < stage_last ? 2048 : 0;   // the weight stage is clamped to the last one
 #pragma unroll
-    for (int i = 0; i < NLB; ++i) lds_dma16(Wp + (boff[i] + kb), sa + ABYTES + (i * NW + wave) * 1024);
+    for (int i = 0; i < NLB; ++i) {
+      lds_dma16(bptr[i], sa + ABYTES + (i * NW + wave) * 1024);
+      bptr[i] += bstep;
+    }
     ++l_stage;
     l_c += 64;
-    if (l_c >= Ct) {
-      l_c = 0;
-      if (++l_kx == p.ksize) { l_kx = 0; ++l_ky; }
+    if (l_c == p.C1 || l_c >= Ct) {       // next source of a concatenation, or next tap
+      if (l_c >= Ct) {
+        l_c = 0;
+        if (++l_kx == p.ksize) { l_kx = 0; ++l_ky; }
+      }
       set_tap();
     }
   };
@@ -435,12 +443,14 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
     a_x[mt] = (r >> 1) & 7;
   }
 
-  issue(0);
-  issue(1);
+#pragma unroll
+  for (int b = 0; b < NBUF; ++b) issue(b);
   int buf = 0;
   for (int s = 0; s < nstages; ++s) {
-    // vmcnt(NLOADS): all but this wave's newest NLOADS loads (stage s+1) have landed, i.e. stage s has
-    __builtin_amdgcn_s_waitcnt(0x0F70 | NLOADS);
+    // all but this wave's newest (NBUF-1)*NLOADS loads (stages s+1 ..) have landed, i.e. stage s has
+    constexpr int PENDING = (NBUF - 1) * NLOADS;
+    static_assert(PENDING < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (PENDING & 15) | ((PENDING >> 4) << 14));
     __syncthreads();                     // ... and everyone else's part of stage s too
     const unsigned char* sa = lds + buf * STAGE;
     const unsigned char* sb = sa + ABYTES;
@@ -454,7 +464,7 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
       for (int nt = 0; nt < NT; ++nt) bfr[ks][nt] = *(const bf16x8*)(sb + ((wn * NT + nt) * 2 + ks) * 1024 + lane * 16);
     }
     __syncthreads();                     // every wave holds its fragments: the buffer can be refilled
-    issue(buf);                          // stage s+2
+    issue(buf);                          // stage s+NBUF
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
@@ -462,7 +472,7 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
           acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[ks][nt], af[ks][mt], acc[mt][nt], 0, 0, 0);
-    buf ^= 1;
+    buf = buf + 1 == NBUF ? 0 : buf + 1;
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);  // the prefetches past the end must land before the block's LDS is released
   epilogue<MT, NT>(p, acc, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo, tile.split);
@@ -475,15 +485,26 @@ __global__ __launch_bounds__(256) void igemm_finalize_kernel(IgemmParams p) {
   if (idx4 >= total4) return;
   const long long e = idx4 * 4;
   const int m = (int)(e / p.N), n = (int)(e - (long long)m * p.N);
+  // the kernel is one latency chain per thread: issue every independent load before the first add
+  const long long plane = (long long)p.M * p.N;
+  f32x4 add = {0.f, 0.f, 0.f, 0.f};
+  if (p.bias) add = *(const f32x4*)(p.bias + n);
+  if (p.rowbias) add += *(const f32x4*)(p.rowbias + (long long)(m / (p.Hout * p.Wout)) * p.rowbias_ld + n);
+  bf16x4 r = {(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
+  if (p.residual) r = *(const bf16x4*)((const bf16_t*)p.residual + e);
   f32x4 x = *(const f32x4*)(p.workspace + e);
-  for (int z = 1; z < p.splitk; ++z) x += *(const f32x4*)(p.workspace + (long long)z * p.M * p.N + e);
-  if (p.bias) x += *(const f32x4*)(p.bias + n);
-  if (p.rowbias) x += *(const f32x4*)(p.rowbias + (long long)(m / (p.Hout * p.Wout)) * p.rowbias_ld + n);
-  if (p.residual) {
-    bf16x4 r = *(const bf16x4*)((const bf16_t*)p.residual + e);
-#pragma unroll
-    for (int v = 0; v < 4; ++v) x[v] += (float)r[v];
+  int z = 1;
+  for (; z + 4 <= p.splitk; z += 4) {   // same order of additions as one by one
+    const f32x4 a = *(const f32x4*)(p.workspace + (long long)z * plane + e);
+    const f32x4 b = *(const f32x4*)(p.workspace + (long long)(z + 1) * plane + e);
+    const f32x4 c = *(const f32x4*)(p.workspace + (long long)(z + 2) * plane + e);
+    const f32x4 d = *(const f32x4*)(p.workspace + (long long)(z + 3) * plane + e);
+    x += a; x += b; x += c; x += d;
   }
+  for (; z < p.splitk; ++z) x += *(const f32x4*)(p.workspace + (long long)z * plane + e);
+  x += add;
+#pragma unroll
+  for (int v = 0; v < 4; ++v) x[v] += (float)r[v];
   bf16x4 o;
 #pragma unroll
   for (int v = 0; v < 4; ++v) o[v] = (bf16_t)x[v];
@@ -503,11 +524,11 @@ template <int BM, int BN, int NSETS> void launch_cfg(const IgemmParams& p, hipSt
   }
 }
 
-template <int BM, int BN> void launch_dma(const IgemmParams& p, hipStream_t s) {
-  constexpr int LDS = 2 * (BM + BN) * 128;
+template <int BM, int BN, int NBUF> void launch_dma(const IgemmParams& p, hipStream_t s) {
+  constexpr int LDS = NBUF * (BM + BN) * 128;
   static bool attr_set = false;
   if (!attr_set) {
-    hipFuncSetAttribute((const void*)igemm_dma_kernel<BM, BN>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    hipFuncSetAttribute((const void*)igemm_dma_kernel<BM, BN, NBUF>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     attr_set = true;
   }
   const int mtiles = (p.M + BM - 1) / BM, ntiles = (p.N + BN - 1) / BN;
@@ -516,7 +537,7 @@ template <int BM, int BN> void launch_dma(const IgemmParams& p, hipStream_t s) {
   const int splitk = p.splitk > 1 ? p.splitk : 1;
   const int sps = (total_stages + splitk - 1) / splitk;
   dim3 grid((mtiles * ntiles * splitk + 7) & ~7);
-  hipLaunchKernelGGL((igemm_dma_kernel<BM, BN>), grid, dim3(256), LDS, s, p, mtiles, ksteps_total, sps);
+  hipLaunchKernelGGL((igemm_dma_kernel<BM, BN, NBUF>), grid, dim3(256), LDS, s, p, mtiles, ksteps_total, sps);
   if (splitk > 1) {
     long long total4 = (long long)p.M * p.N / 4;
     hipLaunchKernelGGL(igemm_finalize_kernel, dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s, p);
@@ -572,7 +593,7 @@ Choice choose(const IgemmParams& p) {
   if (const char* t = getenv("SDSTREAM_TUNE")) {  // "variant,bn,splitk" for sweeps; unsupported combinations are ignored
     int v = -1, bn = 0, sk = 0;
     if (sscanf(t, "%d,%d,%d", &v, &bn, &sk) == 3) {
-      if (v >= 0 && v <= 2 && (k64 || v == 0)) c.variant = v;
+      if (v >= 0 && v <= 4 && (k64 || v == 0)) c.variant = v;
       if ((bn == 160 || bn == 128 || bn == 64) && !(p.epilogue == EPI_GEGLU && bn == 160)) c.bn = bn;
       if (sk >= 1 && may_split && (long long)sk * p.M * p.N <= p.workspace_floats &&
           sk <= (c.variant == 0 ? p.K / 32 : p.K / 64))
@@ -584,8 +605,10 @@ Choice choose(const IgemmParams& p) {
 
 template <int BN> void launch_bn(const IgemmParams& p, int variant, hipStream_t s) {
   switch (variant) {
-    case 1: launch_dma<128, BN>(p, s); break;
-    case 2: launch_dma<64, BN>(p, s); break;
+    case 1: launch_dma<128, BN, 2>(p, s); break;
+    case 2: launch_dma<64, BN, 2>(p, s); break;
+    case 3: launch_dma<64, BN, 4>(p, s); break;
+    case 4: launch_dma<128, BN, 3>(p, s); break;
     default: launch_cfg<128, BN, 3>(p, s); break;
   }
 }

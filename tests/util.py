@@ -15,18 +15,18 @@ def rel_l2(g, o):
     return float(np.linalg.norm(g - o) / np.linalg.norm(o))
 
 
-def oracle_net(wl, bf16_weights):
+def oracle_net(wl, bf16_weights, cross_frame=False):
     from oracle import unet as U
     shape = U.UNetShape.from_dict(wl["unet"])
     blob = make_weights(U.manifest(shape), wl["seeds"]["weights"], wl["init"], bf16_weights)
-    return U.UNet(shape, blob)
+    return U.UNet(shape, blob, cross_frame=cross_frame)
 
 
-def gpu_engine(wl, dtype, cfg_mode=0, scheduler=0, n_streams=None, timesteps=None, blob=None):
+def gpu_engine(wl, dtype, cfg_mode=0, scheduler=0, n_streams=None, timesteps=None, blob=None, cross_frame=0):
     import paper_2312_12491_amd as sd
     ts = wl["timesteps"] if timesteps is None else timesteps
     S = wl["n_streams"] if n_streams is None else n_streams
-    cfg = sd.config_from_dict(wl["unet"], wl["latent"], dtype, len(ts), S, cfg_mode, scheduler)
+    cfg = sd.config_from_dict(wl["unet"], wl["latent"], dtype, len(ts), S, cfg_mode, scheduler, cross_frame)
     eng = sd.Engine(cfg)
     if blob is None:
         blob = make_weights(eng.manifest(), wl["seeds"]["weights"], wl["init"], dtype == "bf16")
