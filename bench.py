@@ -32,6 +32,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, help="workload number (2..5); 3 = SD-1.5 shape, B=4, 512^2")
     ap.add_argument("--mode", type=int, default=-1, help="override cfg_mode (0 none,1 CFG,2 self,3 onetime)")
+    ap.add_argument("--cross-frame", action="store_true",
+                    help="Stream Batch cross-frame attention (Sec. 3.2): self-attention over the keys of all n rows")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=3)
@@ -59,7 +61,7 @@ def main():
         mode = mode[1]
     ts = list(wl["timesteps"])
     n, S = len(ts), wl["n_streams"]
-    cfg = sd.config_from_dict(wl["unet"], wl["latent"], wl["dtype"], n, S, mode)
+    cfg = sd.config_from_dict(wl["unet"], wl["latent"], wl["dtype"], n, S, mode, 0, int(args.cross_frame))
     eng = sd.Engine(cfg)
     blob = make_weights(eng.manifest(), wl["seeds"]["weights"], wl["init"], wl["dtype"] == "bf16")
     eng.load_weights(blob)
@@ -124,7 +126,7 @@ def main():
     achieved = dr["flops"] / dr["launches"] / (launch_us * 1e-6) / 1e12
     # HBM-side bytes per launch of this kernel class, from the two rocprofv3 --pmc passes summarised under profiles/
     # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 256 MiB copy); only valid for the workload they were taken on
-    traffic = TRAFFIC_BYTES_PER_LAUNCH.get((args.config, mode)) if dom == "igemm_mfma" else None
+    traffic = TRAFFIC_BYTES_PER_LAUNCH.get((args.config, mode)) if dom == "igemm_mfma" and not args.cross_frame else None
     roofline = {"kernel": dom, "bound": "mfma" if dom.endswith("mfma") else "alu",
                 "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                 "avg_launch_us": launch_us, "event_pair_overhead_us": pair_us,
@@ -132,7 +134,7 @@ def main():
                 "algorithmic_bytes_per_launch": dr["bytes"] / dr["launches"], "traffic": traffic}
 
     cpu_baseline = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.cross_frame:   # (a cross-frame batch has no one-row sample)
         from oracle import unet as U
         shape = U.UNetShape.from_dict(wl["unet"])
         net = U.UNet(shape, blob)
@@ -149,7 +151,8 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": wl["dtype"], "data": "synthetic",
         "config": {"workload": f"config {args.config}: {wl['name']}, latent {wl['latent'][0]}x{wl['latent'][1]}, "
-                               f"n={n} steps x S={S} streams, cfg_mode={mode}, U-Net batch {rows}",
+                               f"n={n} steps x S={S} streams, cfg_mode={mode}, U-Net batch {rows}"
+                               + (", cross-frame attention" if args.cross_frame else ""),
                    "timesteps": ts, "graph": not args.no_graph},
         "unet_step_ms": ms_per_step, "step_tflop": step_flops / 1e12, "mfma_util": util,
         "peak_assumed_tflops": PEAK_BF16_TFLOPS,

@@ -107,7 +107,10 @@ int sdstream_step(sdstream_t* h, const float* x0_in, const float* context, const
 
 /* The U-Net alone (the eps_theta of Sec. 3.1), for checking it apart from the queue:
  *   x device [N,C,H,W], t host [N] in [0,999], ctx device [L,D], eps_out device [N,C,H,W];
- *   1 <= N <= sdstream_max_batch(h).  Does not touch the queue. */
+ *   1 <= N <= sdstream_max_batch(h).  Does not touch the queue.
+ *   With cross_frame = 1 (Sec. 3.2) every complete run of n_denoise consecutive rows is one stream batch whose rows
+ *   share self-attention keys and values; rows left over at the end stay alone.  (In sdstream_step the batches are
+ *   the n rows of a stream, the positive- and, under CFG_FULL, the negative-prompt rows each among themselves.) */
 int sdstream_unet_forward(sdstream_t* h, const float* x, const int32_t* t, const float* ctx, int32_t n,
                           float* eps_out, void* hip_stream);
 int32_t sdstream_max_batch(const sdstream_t* h);

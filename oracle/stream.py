@@ -10,6 +10,10 @@ Readings of points the paper leaves open (each also listed in the design notes):
   * c_skip = 0, c_out = 1 (the constants the paper says it uses, Sec. 3.3 and the appendix on pre-computation).
   * next latent: re-noise x0_hat to tau_{i+1} with the cached noise of step i+1 (appendix, pre-computation);
     scheduler 'ddim' uses the guided eps instead of cached noise.
+  * scheduler 'lcm_exact': the consistency parameterisation of the appendix evaluated instead of replaced by
+    (0, 1): x0_hat = c_skip(tau_i) x_i + c_out(tau_i) (x_i - b_i eps)/a_i, with sigma_data = 0.5, s = 10 and the
+    c_out that has the limits the text states (see c_skip_c_out); at tau = 0 this is the boundary condition
+    x0_hat = x.  Eq. 5 (virtual residual noise) is left as the paper derives it, under (0, 1).
   * the reference latent of Eq. 5 travels with its frame through the queue.
   * onetime-negative: Eq. 5 is applied at every slot including 0, with the reference of Eq. 7.
   * the queue starts at zero; the first n-1 outputs are flagged invalid.
@@ -114,8 +118,11 @@ class StreamBatch:
                 else:
                     G = rcfg(virtual_residual_noise(x[i], ref[i], a[i], b[i]), E[i], self.gamma, self.delta)
                 X0 = predict_x0(x[i], G, a[i], b[i])
+                if self.scheduler == "lcm_exact":        # f = c_skip x + c_out F of the appendix, not its (0, 1) shortcut
+                    cs, co = c_skip_c_out(self.t[i])
+                    X0 = cs * x[i] + co * X0
                 if i < n - 1:
-                    nxt = self.noise[i + 1, s] if self.scheduler == "lcm" else G
+                    nxt = G if self.scheduler == "ddim" else self.noise[i + 1, s]
                     self.q[s, i] = add_noise(X0, nxt, a[i + 1], b[i + 1])
                     if ref[i] is not None:
                         self.r[s, i] = ref[i]
@@ -155,6 +162,9 @@ def sequential_denoise(eps_fn: EpsFn, x0, timesteps: Sequence[int], noise, ctx, 
         else:
             g = e
         x0_hat = (x - b[i] * g) / a[i]
+        if scheduler == "lcm_exact":
+            cs, co = c_skip_c_out(t[i])
+            x0_hat = cs * x + co * x0_hat
         if i + 1 < len(t):
-            x = a[i + 1] * x0_hat + b[i + 1] * (noise[i + 1] if scheduler == "lcm" else g)
+            x = a[i + 1] * x0_hat + b[i + 1] * (g if scheduler == "ddim" else noise[i + 1])
     return x0_hat

@@ -5,7 +5,8 @@ costs the float64 oracle ~10 s per row on 8 cores, so these prefixes are compute
 tests compare against the stored arrays:
   config 2: first 2 frames;  config 3: first 6 frames (3 valid outputs);  config 4: first 6 frames in each of
   the three guidance modes;  config 5: first 5 frames of stream 0 (2 valid outputs);  plus one raw eps row
-  (t = 999) per U-Net shape.
+  (t = 999) per U-Net shape;  "3x": config 3 with Stream Batch cross-frame attention (Sec. 3.2), first 5 frames
+  (2 valid outputs), into config3_xframe.npz.
 Usage: python tests/golden/make_golden.py [config ...]
 """
 import os
@@ -25,12 +26,13 @@ from workloads import CONFIGS, make_weights, stream_inputs  # noqa: E402
 FRAMES = {2: 2, 3: 6, 4: 6, 5: 5}
 
 
-def run(c: int):
+def run(c: int, cross_frame: bool = False):
     wl = CONFIGS[c]
     shape = U.UNetShape.from_dict(wl["unet"])
     t0 = time.time()
-    net = U.UNet(shape, make_weights(U.manifest(shape), wl["seeds"]["weights"], wl["init"], wl["dtype"] == "bf16"))
-    frames = FRAMES[c]
+    net = U.UNet(shape, make_weights(U.manifest(shape), wl["seeds"]["weights"], wl["init"], wl["dtype"] == "bf16"),
+                 cross_frame=cross_frame)
+    frames = 5 if cross_frame else FRAMES[c]
     inp = stream_inputs(wl, frames)
     ctx, neg = torch.as_tensor(inp["context"]), torch.as_tensor(inp["neg_context"])
     ts = list(wl["timesteps"])
@@ -45,9 +47,9 @@ def run(c: int):
             out[f"mode{mode}_frame{k}"] = o.numpy().astype(np.float32)
             out[f"mode{mode}_valid{k}"] = np.bool_(valid)
             print(f"config {c} mode {mode} frame {k} valid={valid} ({time.time() - t0:.0f} s)", flush=True)
-    np.savez_compressed(os.path.join(HERE, f"config{c}.npz"), **out)
+    np.savez_compressed(os.path.join(HERE, f"config{c}_xframe.npz" if cross_frame else f"config{c}.npz"), **out)
 
 
 if __name__ == "__main__":
-    for c in ([int(a) for a in sys.argv[1:]] or [2, 3, 4, 5]):
-        run(c)
+    for a in (sys.argv[1:] or ["2", "3", "4", "5", "3x"]):
+        run(int(a.rstrip("x")), a.endswith("x"))

@@ -25,7 +25,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 def _golden(c):
     path = os.path.join(HERE, "golden", f"config{c}.npz")
     if not os.path.exists(path):
-        pytest.skip(f"{path} missing: run tests/golden/make_golden.py {c}")
+        pytest.skip(f"{path} missing: run tests/golden/make_golden.py {str(c).replace('_xframe', 'x')}")
     return np.load(path)
 
 
@@ -65,13 +65,13 @@ def _sequential_on_gpu(eng, x0, ts, noise, ctx, neg, mode, gamma, delta):
     return x0_hat
 
 
-def _run_stream(c, mode, frames, check_seq=()):
+def _run_stream(c, mode, frames, check_seq=(), cross_frame=0):
     wl = CONFIGS[c]
-    gold = _golden(c)
+    gold = _golden(f"{c}_xframe" if cross_frame else c)
     ts = list(wl["timesteps"])
     n, S = len(ts), wl["n_streams"]
     inp = stream_inputs(wl, frames)
-    eng = gpu_engine(wl, "bf16", cfg_mode=mode)
+    eng = gpu_engine(wl, "bf16", cfg_mode=mode, cross_frame=cross_frame)
     eng.set_noise(inp["noise"])
     ctx, neg = cuda(inp["context"]), cuda(inp["neg_context"])
     out = torch.empty(S, *inp["x0"].shape[2:], device="cuda")
@@ -122,6 +122,12 @@ def test_config3_stream_batch_of_four():
     errs, seq = _run_stream(3, 0, 40, check_seq=[(2, 0), (33, 0)])
     assert max(errs) <= TOL_BF16
     assert max(seq) <= TOL_SEQ
+
+
+def test_config3_cross_frame_attention():
+    # Sec. 3.2 at full size: every level-0 self-attention runs over 4 x 4096 keys
+    errs, _ = _run_stream(3, 0, 8, cross_frame=1)
+    assert len(errs) == 2 and max(errs) <= TOL_BF16
 
 
 @pytest.mark.parametrize("mode", [1, 2, 3])

@@ -110,7 +110,7 @@ def _run_stream(eps_fn, ts, mode, gamma, delta, frames, S_=1, sched="lcm", seed=
 
 @pytest.mark.parametrize("mode", [S.MODE_NONE, S.MODE_CFG, S.MODE_SELF, S.MODE_ONETIME])
 @pytest.mark.parametrize("ts", [(999,), (999, 499), (999, 759, 499, 259)])
-@pytest.mark.parametrize("sched", ["lcm", "ddim"])
+@pytest.mark.parametrize("sched", ["lcm", "ddim", "lcm_exact"])
 def test_stream_batch_equals_sequential(mode, ts, sched):
     n, frames, ns = len(ts), 7, 2
     x0, noise, ctx, neg, outs = _run_stream(toy_eps, ts, mode, 1.3, 0.8, frames, ns, sched)
@@ -260,3 +260,35 @@ def test_ssf_uniform_draws():
     for p in (0.1, 0.46, 0.89):
         rate = (us < p).mean()
         assert abs(rate - p) < 3 * math.sqrt(p * (1 - p) / len(us)) + 1e-3
+
+
+# ------------------------------------------------------------------ exact consistency parameterisation
+def test_exact_parameterisation_known_values_and_boundary():
+    # appendix: c_skip = sd^2 / ((s tau)^2 + sd^2), c_out = s tau / sqrt(sd^2 + (s tau)^2) with sd = 0.5, s = 10
+    cs, co = S.c_skip_c_out(0)
+    assert (cs, co) == (1.0, 0.0)                          # boundary condition f(x, 0) = x
+    cs, co = S.c_skip_c_out(1)
+    assert abs(cs - 0.25 / 100.25) < 1e-15 and abs(co - 10.0 / 100.25 ** 0.5) < 1e-15
+    cs, co = S.c_skip_c_out(259)
+    assert cs < 4e-8 and 1 - co < 2e-8                     # the (0, 1) constants the paper uses are exact to fp32
+
+
+def test_exact_parameterisation_is_the_shortcut_at_the_papers_timesteps_and_the_identity_at_zero():
+    ts = (999, 759, 499, 259)
+    _, _, _, _, a = _run_stream(toy_eps, ts, S.MODE_SELF, 1.2, 1.0, 6, 1, "lcm")
+    _, _, _, _, b = _run_stream(toy_eps, ts, S.MODE_SELF, 1.2, 1.0, 6, 1, "lcm_exact")
+    for (oa, va), (ob, vb) in zip(a, b):
+        assert va == vb
+        if va:
+            assert 0 < (oa - ob).abs().max() <= 1e-6 * oa.abs().max()
+    # a last step at tau = 0 hands its input latent through unchanged: x0_hat = 1 * x + 0 * (...)
+    ts0 = (500, 0)
+    x0, noise, ctx, neg, outs = _run_stream(toy_eps, ts0, S.MODE_NONE, 1.0, 1.0, 4, 1, "lcm_exact")
+    a_, b_ = S.ab(ts0)
+    for k in range(1, 4):
+        f = k - 1
+        x = a_[0] * x0[f, 0] + b_[0] * noise[0, 0]
+        e = toy_eps(x[None], [500], ctx)[0]
+        cs, co = S.c_skip_c_out(500)
+        x_at_0 = a_[1] * (cs * x + co * (x - b_[0] * e) / a_[0]) + b_[1] * noise[1, 0]
+        np.testing.assert_allclose(outs[k][0][0].numpy(), x_at_0.numpy(), rtol=0, atol=1e-12)
