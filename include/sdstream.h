@@ -61,7 +61,9 @@ typedef struct {
   int32_t n_denoise;                            /* n = Stream Batch size = denoising steps                     */
   int32_t n_streams;                            /* S independent streams sharing weights, noise and prompt     */
   int32_t cfg_mode;                             /* SDSTREAM_CFG_*                                              */
-  int32_t scheduler;                            /* 0: LCM re-noising with the cached noise; 1: DDIM (eta = 0)  */
+  int32_t scheduler;                            /* 0: LCM re-noising with the cached noise; 1: DDIM (eta = 0); */
+                                                /* 2: as 0 with x0 = c_skip(tau) x + c_out(tau) (x - b eps)/a,  */
+                                                /*    the appendix's parameterisation instead of its (0,1) form */
   int32_t cross_frame;                          /* 1: Stream Batch cross-frame attention (Sec. 3.2, K_Batch /  */
                                                 /*    V_Batch): every self-attention of a row uses the keys and */
                                                 /*    values of all n rows of its stream (and prompt branch);   */

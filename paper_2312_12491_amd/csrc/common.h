@@ -108,6 +108,8 @@ struct StreamParams {
   float gamma, delta;
   const float* a;        // [n] sqrt(alpha), device
   const float* b;        // [n] sqrt(beta), device
+  const float* cskip;    // [n] c_skip(tau_i), c_out(tau_i) of the consistency parameterisation (scheduler 2)
+  const float* cout;
   const float* noise;    // [n][S][E]
   const float* x0_in;    // [S][E]
   float* xcur;           // [rows][E] U-Net input batch of this call

@@ -541,7 +541,7 @@ struct Builder {
     }
     e.off_eps = palloc((size_t)e.max_batch * e.E * 4);
     e.off_noise = palloc(rows_state * e.E * 4);
-    e.off_ab = palloc((size_t)2 * c.n_denoise * 4);
+    e.off_ab = palloc((size_t)4 * c.n_denoise * 4);   // a, b, c_skip, c_out per slot
     e.off_unet_x = palloc((size_t)e.max_batch * e.E * 4);
     e.off_splitk = palloc(kSplitKWorkspaceFloats * 4);
     e.off_zeros = palloc(256);
@@ -693,7 +693,7 @@ int validate(const sdstream_config& c, std::string& why) {
   if (c.n_denoise < 1 || c.n_denoise > 64) BAD("n_denoise %d out of range", c.n_denoise);
   if (c.n_streams < 1 || c.n_streams > 64) BAD("n_streams %d out of range", c.n_streams);
   if (c.cfg_mode < 0 || c.cfg_mode > 3) BAD("cfg_mode %d", c.cfg_mode);
-  if (c.scheduler < 0 || c.scheduler > 1) BAD("scheduler %d", c.scheduler);
+  if (c.scheduler < 0 || c.scheduler > 2) BAD("scheduler %d", c.scheduler);
   if (c.cross_frame < 0 || c.cross_frame > 1) BAD("cross_frame %d", c.cross_frame);
   for (int l = 0; l < c.n_levels; ++l) {
     int ch = c.block_channels[l];
@@ -1117,10 +1117,15 @@ int sdstream_step(sdstream_t* h, const float* x0_in, const float* context, const
   const int rows = h->max_batch;
   if (ts != h->timesteps) {
     // new schedule points: constants, selection table, and a fresh queue
-    std::vector<float> ab(2 * n);
+    std::vector<float> ab(4 * n);
     for (int i = 0; i < n; ++i) {
       ab[i] = (float)sqrt(h->alphas[ts[i]]);
       ab[n + i] = (float)sqrt(1.0 - h->alphas[ts[i]]);
+      // consistency parameterisation of the appendix (sigma_data = 0.5, s = 10), in the form that has the limits the
+      // text states: c_skip(0) = 1, c_out(0) = 0, and (0, 1) to fp32 accuracy at the timesteps the paper runs
+      const double st = 10.0 * ts[i], sd2 = 0.25;
+      ab[2 * n + i] = (float)(sd2 / (st * st + sd2));
+      ab[3 * n + i] = (float)(st / sqrt(st * st + sd2));
     }
     std::vector<int> sel(rows, 0);
     for (int r = S * n; r < rows; ++r) sel[r] = 1;
@@ -1148,6 +1153,8 @@ int sdstream_step(sdstream_t* h, const float* x0_in, const float* context, const
   p.gamma = gamma; p.delta = delta;
   p.a = (const float*)(h->persist + h->off_ab);
   p.b = p.a + n;
+  p.cskip = p.a + 2 * n;
+  p.cout = p.a + 3 * n;
   p.noise = (const float*)(h->persist + h->off_noise);
   p.x0_in = x0_in;
   p.xcur = (float*)(h->persist + h->off_x[h->cur]);

@@ -228,9 +228,10 @@ __global__ __launch_bounds__(256) void stream_tail_kernel(StreamParams p) {
     float V = (x - a * ref) / b;                      // Eq. 5
     G = p.delta * V + p.gamma * (E - p.delta * V);    // Eq. 6
   }
-  const float X0 = (x - b * G) / a;  // Eq. 4 with c_skip = 0, c_out = 1
+  float X0 = (x - b * G) / a;  // Eq. 4 with c_skip = 0, c_out = 1
+  if (p.scheduler == 2) X0 = p.cskip[i] * x + p.cout[i] * X0;  // the parameterisation itself (appendix)
   if (i < p.n - 1) {
-    float nxt = p.scheduler == 0 ? p.noise[((long long)(i + 1) * p.S + s) * p.E + e] : G;
+    float nxt = p.scheduler == 1 ? G : p.noise[((long long)(i + 1) * p.S + s) * p.E + e];
     p.xnext[idx + p.E] = p.a[i + 1] * X0 + p.b[i + 1] * nxt;
     if (p.mode >= 2) p.rnext[idx + p.E] = ref;
   } else {

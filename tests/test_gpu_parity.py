@@ -59,12 +59,13 @@ def test_unet_mini_bf16(name):
     assert rel_l2(got, want) <= TOL_BF16
 
 
-def _stream_case(wl, dtype, mode, gamma, delta, frames, sched=0, graph=True):
+def _stream_case(wl, dtype, mode, gamma, delta, frames, sched=0, graph=True, swap_prompt_at=None):
+    """swap_prompt_at = k: from call k on the positive and the negative prompt change places (a new context_epoch)."""
     from oracle import stream as S
     net = oracle_net(wl, dtype == "bf16")
     inp = stream_inputs(wl, frames)
     ts = list(wl["timesteps"])
-    sb = S.StreamBatch(net, ts, inp["noise"], mode, gamma, delta, "lcm" if sched == 0 else "ddim")
+    sb = S.StreamBatch(net, ts, inp["noise"], mode, gamma, delta, ("lcm", "ddim", "lcm_exact")[sched])
     ctx, neg = torch.as_tensor(inp["context"]), torch.as_tensor(inp["neg_context"])
     eng = gpu_engine(wl, dtype, cfg_mode=mode, scheduler=sched)
     eng.use_graph(graph)
@@ -73,7 +74,12 @@ def _stream_case(wl, dtype, mode, gamma, delta, frames, sched=0, graph=True):
     out = torch.empty_like(cuda(inp["x0"][0]))
     worst_max, worst_l2, n_valid = 0.0, 0.0, 0
     for k in range(frames):
-        valid = eng.step(cuda(inp["x0"][k]), dctx, dneg, 1, ts, gamma, delta, out)
+        epoch = 1
+        if swap_prompt_at is not None and k == swap_prompt_at:
+            ctx, neg, dctx, dneg = neg, ctx, dneg, dctx
+        if swap_prompt_at is not None and k >= swap_prompt_at:
+            epoch = 2
+        valid = eng.step(cuda(inp["x0"][k]), dctx, dneg, epoch, ts, gamma, delta, out)
         torch.cuda.synchronize()
         want, wvalid = sb.step(inp["x0"][k], ctx, neg)
         assert valid == wvalid
@@ -97,6 +103,26 @@ def test_config1_stream_all_frames():
 def test_stream_modes_mini_fp32(mode, sched):
     wl = MINI_CONFIGS["mini21"]       # 2 streams x 2 steps
     worst, _ = _stream_case(wl, "fp32", mode, 1.3, 0.8, 4, sched, graph=(mode % 2 == 0))
+    assert worst <= TOL_FP32
+
+
+@pytest.mark.parametrize("mode", [0, 2])
+def test_exact_consistency_parameterisation_fp32(mode):
+    # scheduler 2 (c_skip, c_out of the appendix) at timesteps small enough for them to differ from (0, 1):
+    # c_skip(2) = 6.2e-4, and the last slot at tau = 0 is the boundary condition x0 = x
+    wl = dict(MINI_CONFIGS["mini21"], timesteps=(2, 0))
+    worst, _ = _stream_case(wl, "fp32", mode, 1.3, 0.8, 4, 2)
+    assert worst <= TOL_FP32
+    wl = dict(MINI_CONFIGS["mini21"])
+    worst, _ = _stream_case(wl, "fp32", mode, 1.3, 0.8, 3, 2, graph=False)
+    assert worst <= TOL_FP32
+
+
+@pytest.mark.parametrize("mode", [1, 3])
+def test_prompt_change_while_the_queue_is_live_fp32(mode):
+    # the prompt's cached keys / values are rebuilt when context_epoch changes; frames already in the queue go on
+    wl = MINI_CONFIGS["mini15"]       # 1 stream x 4 steps
+    worst, _ = _stream_case(wl, "fp32", mode, 1.3, 0.8, 9, swap_prompt_at=5)
     assert worst <= TOL_FP32
 
 
