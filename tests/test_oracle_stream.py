@@ -292,3 +292,56 @@ def test_exact_parameterisation_is_the_shortcut_at_the_papers_timesteps_and_the_
         cs, co = S.c_skip_c_out(500)
         x_at_0 = a_[1] * (cs * x + co * (x - b_[0] * e) / a_[0]) + b_[1] * noise[1, 0]
         np.testing.assert_allclose(outs[k][0][0].numpy(), x_at_0.numpy(), rtol=0, atol=1e-12)
+
+
+# ------------------------------------------------------------------ hard-threshold filter and run statistics
+def test_hard_threshold_is_the_sign_of_eq9():
+    from oracle import ssf as F
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        a = rng.integers(0, 256, size=(6, 5, 3), dtype=np.uint8)
+        b = np.clip(a.astype(np.int64) + rng.integers(-40, 41, size=a.shape), 0, 255).astype(np.uint8)
+        eta = float(rng.uniform(0.8, 1.0))
+        f = F.Filter(eta, 1, hard=True)
+        assert f(a, 0) == (False, 0.0)                       # no reference yet: never skipped
+        skip, s_c = f(b, 1)
+        d, nt, nr = F.sums(b, a)
+        assert s_c == F.cosine(d, nt, nr)
+        assert skip == (F.skip_probability(s_c, eta) > 0.0)
+    assert F.Filter(1.0, 1, hard=True)(a, 0)[0] is False and not F.Filter(1.0, 1, hard=True)(a, 1)[0]
+
+
+def test_hard_threshold_sticks_where_the_sampled_filter_moves_on():
+    # a scene that drifts slowly away from the first frame: every frame stays within eta of the FIRST one, so the
+    # hard threshold never lets a frame through again, while Eq. 9 lets frames through with probability 1 - P
+    from oracle import ssf as F
+    base = np.full((8, 8, 3), 128, dtype=np.uint8)
+    frames = []
+    for k in range(400):
+        f = base.copy()
+        f[0, 0, 0] = 128 + (k % 100)                         # tiny change, similarity stays > 0.999
+        frames.append(f)
+    hard, soft = F.Filter(0.98, 9, hard=True), F.Filter(0.98, 9)
+    hs = F.run_statistics([hard(f, k)[0] for k, f in enumerate(frames)])
+    ss = F.run_statistics([soft(f, k)[0] for k, f in enumerate(frames)])
+    assert hs == {"frames": 400, "processed": 1, "duty_cycle": 1 / 400, "longest_skip_run": 399}
+    # with S_C = 1 - O(1e-6), P is about 0.9999: the sampled filter is nearly as sparse here, but a scene at
+    # S_C = 0.99 (P = 0.5) must come through about half the time
+    frames2 = []
+    rng = np.random.default_rng(3)
+    ref = rng.integers(0, 256, size=(16, 16, 3), dtype=np.uint8)
+    for k in range(2000):
+        frames2.append(ref if k % 2 == 0 else np.clip(ref.astype(np.int64) + rng.integers(-36, 37, size=ref.shape), 0, 255).astype(np.uint8))
+    soft = F.Filter(0.98, 11)
+    sk, ps = zip(*[soft(f, k) for k, f in enumerate(frames2)])
+    expect = sum(1.0 - p for p in ps)                        # expected number of processed frames given the P's seen
+    var = sum(p * (1.0 - p) for p in ps)
+    assert abs((len(sk) - sum(sk)) - expect) <= 5.0 * max(var, 1.0) ** 0.5
+    assert F.run_statistics(sk)["duty_cycle"] > hs["duty_cycle"]
+
+
+def test_run_statistics_known_cases():
+    from oracle import ssf as F
+    assert F.run_statistics([]) == {"frames": 0, "processed": 0, "duty_cycle": 0.0, "longest_skip_run": 0}
+    assert F.run_statistics([False, True, True, False, True]) == {"frames": 5, "processed": 2, "duty_cycle": 0.4,
+                                                                  "longest_skip_run": 2}
