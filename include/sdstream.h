@@ -132,6 +132,15 @@ int sdstream_ssf(sdstream_t* h, const uint8_t* frame, int32_t height, int32_t wi
 int sdstream_ssf_decide(uint64_t dot, uint64_t n_t, uint64_t n_ref, double eta, uint64_t seed, uint64_t frame_index,
                         double* prob);
 
+/* The hard-threshold filter the paper compares the sampled one with (note at the end of Sec. 3.4; Table 3): skip
+ * exactly when S_C > eta, i.e. when Eq. 9 gives a positive probability; nothing is drawn.  Same reduction kernel,
+ * same reference-frame rule (only a frame that is let through becomes the reference; the first frame always is).
+ * *similarity gets S_C (0 while there is no reference).  The two filters share the engine's reference frame: use
+ * one of them per engine, or call sdstream_reset in between. */
+int sdstream_ssf_decide_hard(uint64_t dot, uint64_t n_t, uint64_t n_ref, double eta, double* similarity);
+int sdstream_ssf_hard(sdstream_t* h, const uint8_t* frame, int32_t height, int32_t width, double eta, int32_t* skip,
+                      double* similarity, void* hip_stream);
+
 /* Clears the queue, the reference latents, the filter's reference frame and the warm-up counter. */
 int sdstream_reset(sdstream_t* h);
 

@@ -54,6 +54,9 @@ _SIGNATURES = {
                                C.POINTER(C.c_int32), C.POINTER(C.c_double), C.c_void_p]),
     "sdstream_ssf_decide": (C.c_int, [C.c_uint64, C.c_uint64, C.c_uint64, C.c_double, C.c_uint64, C.c_uint64,
                                       C.POINTER(C.c_double)]),
+    "sdstream_ssf_decide_hard": (C.c_int, [C.c_uint64, C.c_uint64, C.c_uint64, C.c_double, C.POINTER(C.c_double)]),
+    "sdstream_ssf_hard": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.POINTER(C.c_int32),
+                                    C.POINTER(C.c_double), C.c_void_p]),
     "sdstream_reset": (C.c_int, [C.c_void_p]),
     "sdstream_flops_per_row": (C.c_double, [C.c_void_p]),
     "sdstream_profile_enable": (C.c_int, [C.c_void_p, C.c_int32]),
@@ -106,6 +109,12 @@ def ssf_decide(dot: int, n_t: int, n_ref: int, eta: float, seed: int, frame_inde
     p = C.c_double()
     skip = lib().sdstream_ssf_decide(dot, n_t, n_ref, eta, seed, frame_index, C.byref(p))
     return bool(skip), p.value
+
+
+def ssf_decide_hard(dot: int, n_t: int, n_ref: int, eta: float):
+    sc = C.c_double()
+    skip = lib().sdstream_ssf_decide_hard(dot, n_t, n_ref, eta, C.byref(sc))
+    return bool(skip), sc.value
 
 
 def _ptr(t) -> Optional[int]:
@@ -205,6 +214,13 @@ class Engine:
         self._check(self._l.sdstream_ssf(self._h, _ptr(frame), height, width, eta, seed, frame_index, C.byref(skip),
                                          C.byref(p), stream or None))
         return bool(skip.value), p.value
+
+    def ssf_hard(self, frame, height: int, width: int, eta: float, stream: int = 0):
+        """Hard-threshold filter.  frame: torch uint8 CUDA tensor [H, W, 3].  Returns (skip, similarity)."""
+        skip, sc = C.c_int32(), C.c_double()
+        self._check(self._l.sdstream_ssf_hard(self._h, _ptr(frame), height, width, eta, C.byref(skip), C.byref(sc),
+                                              stream or None))
+        return bool(skip.value), sc.value
 
     # ---- profiling
     def profile_enable(self, on: bool):

@@ -1195,14 +1195,26 @@ int sdstream_ssf_decide(uint64_t dot, uint64_t n_t, uint64_t n_ref, double eta, 
   return u < p ? 1 : 0;
 }
 
-int sdstream_ssf(sdstream_t* h, const uint8_t* frame, int32_t height, int32_t width, double eta, uint64_t seed,
-                 uint64_t frame_index, int32_t* skip, double* prob, void* hip_stream) {
-  if (!h) return SDSTREAM_E_INVALID_ARG;
-  if (!frame || !skip) return fail(h, SDSTREAM_E_INVALID_ARG, "null argument");
+int sdstream_ssf_decide_hard(uint64_t dot, uint64_t n_t, uint64_t n_ref, double eta, double* similarity) {
+  double sc = 0.0;
+  if (n_t != 0 && n_ref != 0) {
+    sc = (double)dot / sqrt((double)n_t * (double)n_ref);
+    if (sc > 1.0) sc = 1.0;
+  }
+  if (similarity) *similarity = sc;
+  return (n_t != 0 && n_ref != 0 && sc > eta) ? 1 : 0;
+}
+
+}  // extern "C"
+
+namespace {
+// the device half of both filters: exact integer sums of the frame against the reference frame; the frame is
+// copied into the spare buffer on the way, so letting it through afterwards is a pointer swap
+int ssf_measure(sdstream* h, const uint8_t* frame, int32_t height, int32_t width, hipStream_t s, uint64_t* dot,
+                uint64_t* nt, bool* have_ref, int* spare_out) {
   if (height < 1 || width < 1) return fail(h, SDSTREAM_E_SHAPE, "frame %dx%d", height, width);
   if (((uintptr_t)frame) & 15) return fail(h, SDSTREAM_E_INVALID_ARG, "frame must be 16-byte aligned");
   const long long n = (long long)height * width * 3;
-  hipStream_t s = (hipStream_t)hip_stream;
   if (n != h->ssf_n) {
     HIP_TRY(h, hipDeviceSynchronize());
     for (int i = 0; i < 2; ++i) {
@@ -1220,16 +1232,54 @@ int sdstream_ssf(sdstream_t* h, const uint8_t* frame, int32_t height, int32_t wi
   launch_ssf_reduce(frame, ref, h->ssf_buf[spare], n, h->ssf_sums, s);
   HIP_TRY(h, hipMemcpyAsync(h->ssf_host, h->ssf_sums, 2 * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
   HIP_TRY(h, hipStreamSynchronize(s));
-  const uint64_t dot = h->ssf_host[0], nt = h->ssf_host[1];
+  *dot = h->ssf_host[0];
+  *nt = h->ssf_host[1];
+  *have_ref = ref != nullptr;
+  *spare_out = spare;
+  return SDSTREAM_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int sdstream_ssf(sdstream_t* h, const uint8_t* frame, int32_t height, int32_t width, double eta, uint64_t seed,
+                 uint64_t frame_index, int32_t* skip, double* prob, void* hip_stream) {
+  if (!h) return SDSTREAM_E_INVALID_ARG;
+  if (!frame || !skip) return fail(h, SDSTREAM_E_INVALID_ARG, "null argument");
+  uint64_t dot, nt;
+  bool have_ref;
+  int spare;
+  int rc = ssf_measure(h, frame, height, width, (hipStream_t)hip_stream, &dot, &nt, &have_ref, &spare);
+  if (rc) return rc;
   double p = 0.0;
-  int sk = sdstream_ssf_decide(dot, nt, ref ? h->ssf_ref_norm : 0, eta, seed, frame_index, &p);
-  if (!ref) { sk = 0; p = 0.0; }
+  int sk = sdstream_ssf_decide(dot, nt, have_ref ? h->ssf_ref_norm : 0, eta, seed, frame_index, &p);
+  if (!have_ref) { sk = 0; p = 0.0; }
   if (!sk) {
     h->ssf_ref = spare;
     h->ssf_ref_norm = nt;
   }
   *skip = sk;
   if (prob) *prob = p;
+  return SDSTREAM_OK;
+}
+
+int sdstream_ssf_hard(sdstream_t* h, const uint8_t* frame, int32_t height, int32_t width, double eta, int32_t* skip,
+                      double* similarity, void* hip_stream) {
+  if (!h) return SDSTREAM_E_INVALID_ARG;
+  if (!frame || !skip) return fail(h, SDSTREAM_E_INVALID_ARG, "null argument");
+  uint64_t dot, nt;
+  bool have_ref;
+  int spare;
+  int rc = ssf_measure(h, frame, height, width, (hipStream_t)hip_stream, &dot, &nt, &have_ref, &spare);
+  if (rc) return rc;
+  double sc = 0.0;
+  int sk = have_ref ? sdstream_ssf_decide_hard(dot, nt, h->ssf_ref_norm, eta, &sc) : 0;
+  if (!sk) {
+    h->ssf_ref = spare;
+    h->ssf_ref_norm = nt;
+  }
+  *skip = sk;
+  if (similarity) *similarity = sc;
   return SDSTREAM_OK;
 }
 

@@ -1,0 +1,70 @@
+"""Run statistics of the similarity filters on a frame sequence: duty cycle (share of frames that are let through,
+i.e. of denoising steps the GPU actually runs - what the paper's power measurement reflects, Sec. 3.4) and the longest
+run of consecutive skips (how long the output can stay stuck, the paper's objection to a hard threshold).
+
+    python -m paper_2312_12491_amd.ssf_stats [--frames 600] [--size 512] [--eta 0.98] [--seed 7000]
+
+runs both filters of the library on the synthetic 60 % static / 40 % perturbed sequence and prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from typing import Iterable
+
+
+def statistics(skips: Iterable[bool]) -> dict:
+    skips = [bool(v) for v in skips]
+    longest = cur = 0
+    for v in skips:
+        cur = cur + 1 if v else 0
+        longest = max(longest, cur)
+    n = len(skips)
+    return {"frames": n, "processed": n - sum(skips), "duty_cycle": (n - sum(skips)) / n if n else 0.0,
+            "longest_skip_run": longest}
+
+
+def run_filter(engine, frames, height: int, width: int, eta: float, seed: int, hard: bool):
+    """frames: iterable of torch uint8 CUDA tensors [H, W, 3].  Returns the per-frame skip decisions."""
+    engine.reset()
+    out = []
+    for k, f in enumerate(frames):
+        skip = engine.ssf_hard(f, height, width, eta)[0] if hard else engine.ssf(f, height, width, eta, seed, k)[0]
+        out.append(skip)
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--frames", type=int, default=600)
+    ap.add_argument("--size", type=int, default=512)
+    ap.add_argument("--eta", type=float, default=0.98)
+    ap.add_argument("--seed", type=int, default=7000)
+    args = ap.parse_args()
+    sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    import torch
+    from workloads import CONFIGS, ssf_frames
+    from . import Engine, config_from_dict
+    if not torch.cuda.is_available():
+        sys.exit("ssf_stats: no GPU visible; the filters run in the HIP library only")
+    wl = CONFIGS[1]
+    eng = Engine(config_from_dict(wl["unet"], wl["latent"], "fp32", 1, 1, 0))
+    frames = [torch.as_tensor(f).cuda() for f in ssf_frames(args.seed - 1000, args.frames, args.size, args.size)]
+    res = {"sequence": f"{args.frames} frames {args.size}x{args.size}x3 u8, 12 static + 8 perturbed per cycle",
+           "eta": args.eta}
+    for name, hard in (("ssf", False), ("hard_threshold", True)):
+        t0 = time.perf_counter()
+        skips = run_filter(eng, frames, args.size, args.size, args.eta, args.seed, hard)
+        torch.cuda.synchronize()
+        st = statistics(skips)
+        st["us_per_frame"] = (time.perf_counter() - t0) / args.frames * 1e6
+        res[name] = st
+    print(json.dumps(res))
+    eng.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -57,3 +57,22 @@ def test_ssf_decide_matches_the_oracle():
     assert ssf_decide(0, 0, 5, 0.5, 1, 1) == (False, 0.0)
     assert ssf_decide(25, 25, 25, 0.98, 1, 1)[1] == 1.0
     assert ssf_decide(25, 25, 25, 1.0, 1, 1) == (False, 0.0)
+
+
+def test_ssf_decide_hard_matches_the_oracle():
+    # host half of the hard-threshold filter (no GPU needed): skip exactly when S_C > eta
+    from oracle import ssf as F
+    from paper_2312_12491_amd import ssf_decide_hard
+    rng = np.random.default_rng(12)
+    for k in range(300):
+        a = rng.integers(0, 256, size=200, dtype=np.int64)
+        b = np.clip(a + rng.integers(-30, 31, size=200), 0, 255)
+        d, nt, nr = int((a * b).sum()), int((a * a).sum()), int((b * b).sum())
+        eta = float(rng.uniform(0.9, 1.0))
+        skip, sc = ssf_decide_hard(d, nt, nr, eta)
+        want = F.cosine(d, nt, nr)
+        assert sc == want or abs(sc - want) <= 2.3e-16 * want
+        assert skip == (want > eta)
+    assert ssf_decide_hard(0, 0, 5, 0.5) == (False, 0.0)
+    assert ssf_decide_hard(25, 25, 25, 0.98) == (True, 1.0)
+    assert ssf_decide_hard(25, 25, 25, 1.0) == (False, 1.0)

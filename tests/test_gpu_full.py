@@ -161,3 +161,27 @@ def test_config5_ssf_sequence_bit_exact():
         band += 0.0 < p < 1.0
     assert 0 < skips < spec["frames"] and band > 0
     eng.close()
+
+
+def test_hard_threshold_filter_and_run_statistics_bit_exact():
+    # both filters on the 512-frame sequence: every decision equals the oracle's, hence so do duty cycle and the
+    # longest stuck run; on this sequence the hard threshold processes fewer frames and stays stuck longer
+    from oracle import ssf as F
+    import paper_2312_12491_amd as sd
+    from paper_2312_12491_amd.ssf_stats import run_filter, statistics
+    wl = CONFIGS[1]
+    spec = CONFIGS[5]["ssf"]
+    eng = sd.Engine(sd.config_from_dict(wl["unet"], wl["latent"], "fp32", 1, 1, 0))
+    frames = list(ssf_frames(spec["frame_seed"], spec["frames"], spec["h"], spec["w"]))
+    dev = [cuda(f) for f in frames]
+    stats = {}
+    for hard in (False, True):
+        flt = F.Filter(spec["eta"], spec["draw_seed"], hard=hard)
+        want = [flt(f, k)[0] for k, f in enumerate(frames)]
+        got = run_filter(eng, dev, spec["h"], spec["w"], spec["eta"], spec["draw_seed"], hard)
+        assert got == want
+        stats[hard] = statistics(got)
+        assert stats[hard] == F.run_statistics(want)
+    assert stats[True]["duty_cycle"] <= stats[False]["duty_cycle"]
+    assert stats[True]["longest_skip_run"] >= stats[False]["longest_skip_run"]
+    eng.close()
