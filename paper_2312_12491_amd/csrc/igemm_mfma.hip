@@ -289,9 +289,9 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma_kernel(IgemmParams p, int m
 //
 // Pipeline (NBUF LDS buffers, loads NBUF stages ahead): a wave reads ALL fragments of stage s into registers,
 // the block synchronises, and the buffer is immediately refilled with stage s+NBUF while the MFMAs of stage s
-// run; stages s+1 .. s+NBUF-1 are already in flight in the other buffers.  NBUF = 2 keeps two blocks per compute
-// unit for the long-K layers; the short-K layers are one memory round trip per NBUF stages long, so they take
-// small tiles with NBUF = 4.  The loads are issued from inline assembly and
+// run; stages s+1 .. s+NBUF-1 are already in flight in the other buffers.  NBUF = 2 is what is built: deeper rings
+// (3 buffers with 128-row tiles, 4 with 64-row tiles) were slower on every layer of the SD-shaped net, because the
+// larger LDS footprint leaves a compute unit with fewer resident blocks.  The loads are issued from inline assembly and
 // waited for with explicit vmcnt values (every wave issues the same number per stage), because the compiler
 // would otherwise drain all outstanding loads before each LDS read.
 // ---------------------------------------------------------------------------------------------------
@@ -593,7 +593,7 @@ Choice choose(const IgemmParams& p) {
   if (const char* t = getenv("SDSTREAM_TUNE")) {  // "variant,bn,splitk" for sweeps; unsupported combinations are ignored
     int v = -1, bn = 0, sk = 0;
     if (sscanf(t, "%d,%d,%d", &v, &bn, &sk) == 3) {
-      if (v >= 0 && v <= 4 && (k64 || v == 0)) c.variant = v;
+      if (v >= 0 && v <= 2 && (k64 || v == 0)) c.variant = v;
       if ((bn == 160 || bn == 128 || bn == 64) && !(p.epilogue == EPI_GEGLU && bn == 160)) c.bn = bn;
       if (sk >= 1 && may_split && (long long)sk * p.M * p.N <= p.workspace_floats &&
           sk <= (c.variant == 0 ? p.K / 32 : p.K / 64))
@@ -607,8 +607,6 @@ template <int BN> void launch_bn(const IgemmParams& p, int variant, hipStream_t 
   switch (variant) {
     case 1: launch_dma<128, BN, 2>(p, s); break;
     case 2: launch_dma<64, BN, 2>(p, s); break;
-    case 3: launch_dma<64, BN, 4>(p, s); break;
-    case 4: launch_dma<128, BN, 3>(p, s); break;
     default: launch_cfg<128, BN, 3>(p, s); break;
   }
 }
