@@ -35,8 +35,12 @@ __device__ __forceinline__ float quad_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// DK = ceil(d/32) contraction steps of Q K^T; DT = ceil(d/16) output tiles of P V; QT = query tiles (of 16) per wave
-template <int DK, int DT, int QT>
+// DK = ceil(d/32) contraction steps of Q K^T; DT = ceil(d/16) output tiles of P V; QT = query tiles (of 16) per wave.
+// ONES (head sizes with d % 16 == 8, i.e. padding rows in the last output tile): row d of the V^T tile is set to
+// one, so row d of O^T accumulates the softmax denominator in the matrix core - from the same bf16-rounded
+// probabilities as the numerator, rescaled with it - and the per-tile sum on the vector ALU, which bounds this
+// kernel at small d, goes away.
+template <int DK, int DT, int QT, bool ONES>
 __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
   constexpr int BQ = 4 * QT * 16;
   constexpr int KPITCH = DK * 64 + 16;   // bytes per key row of the K tile
@@ -137,6 +141,10 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
 
   load_tiles(0);
   __syncthreads();  // zero fill done
+  if (ONES && tid < 2 * BKV) {
+    const int b = tid / BKV, key = tid - b * BKV;
+    *(bf16_t*)(smem + b * TILE + KBYTES + d * VPITCH + key * 2) = (bf16_t)1.0f;
+  }
   store_tiles(0);
   __syncthreads();
   int buf = 0;
@@ -188,11 +196,13 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           float e = __builtin_amdgcn_exp2f(fmaf(s[kt][v], sc, -mnew));
-          sum += e;
+          if (!ONES) sum += e;
           pf[t][kt >> 1][(kt & 1) * 4 + v] = (bf16_t)e;
         }
-      sum = quad_sum(sum);
-      lrun[t] = lrun[t] * alpha[t] + sum;
+      if (!ONES) {
+        sum = quad_sum(sum);
+        lrun[t] = lrun[t] * alpha[t] + sum;
+      }
       rescale = rescale || __any(alpha[t] != 1.0f);
     }
     // O^T += V^T P^T : rows = d (16*dt + 4g + v), column = query li.  The old sums are rescaled only when some
@@ -221,9 +231,11 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
   bf16_t* O = (bf16_t*)p.out;
 #pragma unroll
   for (int t = 0; t < QT; ++t) {
+    // ONES: the denominator of query li is element 0 of the last output tile in the lanes with g == 2 (row d)
+    const float l = ONES ? __shfl(o[t][DT - 1][0], 32 + li) : lrun[t];
     const int q = q0 + t * 16 + li;
     if (q >= p.Sq) continue;
-    const float inv = 1.0f / lrun[t];
+    const float inv = 1.0f / l;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
       const int dd = dt * 16 + g * 4;
@@ -236,28 +248,28 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
   }
 }
 
-template <int DK, int DT, int QT> void launch_qt(const AttnParams& p, hipStream_t s) {
+template <int DK, int DT, int QT, bool ONES> void launch_qt(const AttnParams& p, hipStream_t s) {
   constexpr int BQ = 4 * QT * 16;
   constexpr int LDS = 2 * (BKV * (DK * 64 + 16) + DT * 16 * (BKV * 2 + 16));
   static bool attr_set = false;
   if (!attr_set) {
-    hipFuncSetAttribute((const void*)attn_mfma_kernel<DK, DT, QT>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    hipFuncSetAttribute((const void*)attn_mfma_kernel<DK, DT, QT, ONES>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     attr_set = true;
   }
   dim3 grid((p.Sq + BQ - 1) / BQ, p.heads, p.samples);
-  hipLaunchKernelGGL((attn_mfma_kernel<DK, DT, QT>), grid, dim3(256), LDS, s, p);
+  hipLaunchKernelGGL((attn_mfma_kernel<DK, DT, QT, ONES>), grid, dim3(256), LDS, s, p);
 }
 
 // more query tiles per wave amortise the K / V fragment reads; fewer keep small problems spread over the chip
-template <int DK, int DT> void launch_cfg(const AttnParams& p, hipStream_t s) {
+template <int DK, int DT, bool ONES> void launch_cfg(const AttnParams& p, hipStream_t s) {
   static const int force = getenv("SDSTREAM_ATTN_QT") ? atoi(getenv("SDSTREAM_ATTN_QT")) : 0;
   auto blocks = [&](int qt) { return (long long)((p.Sq + 64 * qt - 1) / (64 * qt)) * p.heads * p.samples; };
   int qt = 1;
   if (blocks(2) >= 512) qt = 2;
   if constexpr (DT <= 4) { if (blocks(4) >= 512) qt = 4; }
   if (force) qt = force;
-  if constexpr (DT <= 4) { if (qt == 4) { launch_qt<DK, DT, 4>(p, s); return; } }
-  if (qt == 1) launch_qt<DK, DT, 1>(p, s); else launch_qt<DK, DT, 2>(p, s);
+  if constexpr (DT <= 4) { if (qt == 4) { launch_qt<DK, DT, 4, ONES>(p, s); return; } }
+  if (qt == 1) launch_qt<DK, DT, 1, ONES>(p, s); else launch_qt<DK, DT, 2, ONES>(p, s);
 }
 
 }  // namespace
@@ -272,12 +284,12 @@ bool attention_mfma_supported(const AttnParams& p) {
 
 void launch_attention_mfma(const AttnParams& p, hipStream_t s) {
   switch (p.d) {
-    case 8: case 16: launch_cfg<1, 1>(p, s); break;
-    case 32: launch_cfg<1, 2>(p, s); break;
-    case 40: launch_cfg<2, 3>(p, s); break;
-    case 64: launch_cfg<2, 4>(p, s); break;
-    case 80: launch_cfg<3, 5>(p, s); break;
-    case 160: launch_cfg<5, 10>(p, s); break;
+    case 8: case 16: launch_cfg<1, 1, false>(p, s); break;
+    case 32: launch_cfg<1, 2, false>(p, s); break;
+    case 40: launch_cfg<2, 3, true>(p, s); break;   // 40 = 2 * 16 + 8: row 40 of the last tile is free
+    case 64: launch_cfg<2, 4, false>(p, s); break;
+    case 80: launch_cfg<3, 5, false>(p, s); break;
+    case 160: launch_cfg<5, 10, false>(p, s); break;
     default: break;
   }
 }
