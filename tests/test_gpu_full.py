@@ -13,7 +13,7 @@ import torch
 
 from workloads import CONFIGS, ssf_frames, stream_inputs
 
-from util import cuda, gpu_engine, rel_l2
+from util import cuda, gpu_engine, rel_l2, rel_max
 
 pytestmark = pytest.mark.gpu
 
@@ -122,6 +122,23 @@ def test_config3_stream_batch_of_four():
     errs, seq = _run_stream(3, 0, 40, check_seq=[(2, 0), (33, 0)])
     assert max(errs) <= TOL_BF16
     assert max(seq) <= TOL_SEQ
+
+
+def test_config3_fp32_path_at_full_size():
+    # the float32 kernels on the SD-1.5-shaped net (same bf16-rounded weights as the golden): a tight bound on the
+    # full-size wiring that the bf16 tolerance cannot give
+    from workloads import make_weights
+    wl = CONFIGS[3]
+    gold = _golden(3)
+    inp = stream_inputs(wl, 1)
+    import paper_2312_12491_amd as sd
+    eng = sd.Engine(sd.config_from_dict(wl["unet"], wl["latent"], "fp32", 1, 1, 0))
+    eng.load_weights(make_weights(eng.manifest(), wl["seeds"]["weights"], wl["init"], True))
+    eps = torch.empty(1, 4, 64, 64, device="cuda")
+    eng.unet_forward(cuda(inp["x0"][0][:1]), [999], cuda(inp["context"]), eps)
+    torch.cuda.synchronize()
+    eng.close()
+    assert rel_max(eps.cpu().numpy(), gold["eps_row0"]) <= 1e-4
 
 
 def test_config3_cross_frame_attention():
