@@ -569,7 +569,7 @@ Choice choose(const IgemmParams& p) {
   }
   int nb128 = blocks(128, bn6);
   int sk = 1;
-  if ((stages >= 64 && (long long)stages * nb128 >= 8000) || (nb128 >= 400 && stages >= 10 && p.M >= 4096)) {
+  if ((stages >= 64 && (long long)stages * nb128 >= 8000) || (nb128 >= 400 && stages >= 5 && p.M >= 4096)) {
     // long K or a grid of several rounds: full tiles, split K when the grid is below the chip size
     c.variant = 1;
     c.bn = nb128 >= 400 ? bn6 : bn0;
@@ -580,9 +580,15 @@ Choice choose(const IgemmParams& p) {
     if (stages >= 32) {
       const int nb = blocks(64, c.bn);
       if (nb < 512) sk = 512 / nb < stages / 8 ? 512 / nb : stages / 8;
+      // a split grid does better with full tiles (half as many blocks, each twice the work per weight byte),
+      // as long as enough blocks remain
+      if (sk > 1 && may_split && blocks(128, c.bn) * sk >= 150) c.variant = 1;
     } else {
       // short K (most 1x1 layers): shrink the tile rather than split K
-      if (blocks(64, c.bn) < 512 && p.N % 64 == 0) c.bn = 64;
+      if (blocks(64, c.bn) < 512) {
+        if (!geglu && p.N % 128 == 0 && blocks(64, 128) >= 400) c.bn = 128;
+        else if (p.N % 64 == 0) c.bn = 64;
+      }
       const int nb = blocks(64, c.bn);
       if (nb < 192 && stages >= 16) sk = 512 / nb < stages / 8 ? 512 / nb : stages / 8;
     }
