@@ -64,60 +64,91 @@ __device__ __forceinline__ TileId tile_of_block(int mtiles, int ntiles, int spli
 
 // Epilogue shared by the kernels: lane holds channels n..n+3 (n = (gnt0+nt)*16 + 4*(lane/16)) of pixel
 // m = mbase + mt*16 + lane%16 in acc[mt][nt].
+// Everything the epilogue reads (bias, time-embedding bias, residual) is requested before the first use: with a
+// load and its wait inside the (mt, nt) loops the epilogue was a chain of up to 3*MT*NT memory round trips.
 template <int MT, int NT>
 __device__ __forceinline__ void epilogue(const IgemmParams& p, f32x4 (&acc)[MT][NT], int mbase, int gnt0, int lane,
                                          int HWo, int split) {
   const int Nout = p.epilogue == EPI_GEGLU ? p.N >> 1 : p.N;
   bf16_t* out = (bf16_t*)p.out;
   const bf16_t* res = (const bf16_t*)p.residual;
+  const int ncol = (lane >> 4) * 4;
+  if (p.splitk > 1) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = mbase + mt * 16 + (lane & 15);
+      if (m >= p.M) continue;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const int n = (gnt0 + nt) * 16 + ncol;
+        if (n >= p.N) continue;
+        *(f32x4*)(p.workspace + ((long long)split * p.M + m) * p.N + n) = acc[mt][nt];
+      }
+    }
+    return;
+  }
+  // per-column addends: bias, plus the time-embedding bias when all rows of this wave belong to one sample
+  const int m_last = min(mbase + MT * 16, p.M) - 1;
+  const bool one_sample = p.rowbias != nullptr && m_last >= mbase && mbase / HWo == m_last / HWo;   // wave-uniform
+  f32x4 addv[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int n = min((gnt0 + nt) * 16 + ncol, p.N - 4);   // clamped: columns past N are never stored
+    f32x4 a = {0.f, 0.f, 0.f, 0.f};
+    if (p.bias) a = *(const f32x4*)(p.bias + n);
+    if (one_sample) a += *(const f32x4*)(p.rowbias + (long long)(mbase / HWo) * p.rowbias_ld + n);
+    addv[nt] = a;
+  }
+  if (p.epilogue == EPI_GEGLU) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = mbase + mt * 16 + (lane & 15);
+      if (m >= p.M) continue;
+#pragma unroll
+      for (int nt = 0; nt < NT; nt += 2) {
+        const int n = (gnt0 + nt) * 16 + ncol;
+        if (n >= p.N) continue;
+        const f32x4 a = acc[mt][nt] + addv[nt], g = acc[mt][nt + 1] + addv[nt + 1];
+        bf16x4 o;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) o[v] = (bf16_t)(a[v] * gelu_erf(g[v]));
+        const int oc = ((gnt0 + nt) >> 1) * 16 + ncol;
+        *(bf16x4*)(out + (long long)m * Nout + oc) = o;
+      }
+    }
+    return;
+  }
+  bf16x4 rv[MT][NT];
+  if (res) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = min(mbase + mt * 16 + (lane & 15), p.M - 1);
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const int n = min((gnt0 + nt) * 16 + ncol, p.N - 4);
+        rv[mt][nt] = *(const bf16x4*)(res + (long long)m * Nout + n);
+      }
+    }
+  }
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     const int m = mbase + mt * 16 + (lane & 15);
     if (m >= p.M) continue;
     const int sample = m / HWo;
-    if (p.splitk > 1) {
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        const int n = (gnt0 + nt) * 16 + (lane >> 4) * 4;
-        if (n >= p.N) continue;
-        *(f32x4*)(p.workspace + ((long long)split * p.M + m) * p.N + n) = acc[mt][nt];
+    for (int nt = 0; nt < NT; ++nt) {
+      const int n = (gnt0 + nt) * 16 + ncol;
+      if (n >= p.N) continue;
+      f32x4 x = acc[mt][nt] + addv[nt];
+      if (p.rowbias && !one_sample) x += *(const f32x4*)(p.rowbias + (long long)sample * p.rowbias_ld + n);
+      if (res) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) x[v] += (float)rv[mt][nt][v];
       }
-      continue;
-    }
-    if (p.epilogue == EPI_GEGLU) {
+      bf16x4 o;
 #pragma unroll
-      for (int nt = 0; nt < NT; nt += 2) {
-        const int n = (gnt0 + nt) * 16 + (lane >> 4) * 4;
-        if (n >= p.N) continue;
-        f32x4 a = acc[mt][nt], g = acc[mt][nt + 1];
-        if (p.bias) {
-          a += *(const f32x4*)(p.bias + n);
-          g += *(const f32x4*)(p.bias + n + 16);
-        }
-        bf16x4 o;
-#pragma unroll
-        for (int v = 0; v < 4; ++v) o[v] = (bf16_t)(a[v] * gelu_erf(g[v]));
-        const int oc = ((gnt0 + nt) >> 1) * 16 + (lane >> 4) * 4;
-        *(bf16x4*)(out + (long long)m * Nout + oc) = o;
-      }
-    } else {
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        const int n = (gnt0 + nt) * 16 + (lane >> 4) * 4;
-        if (n >= p.N) continue;
-        f32x4 x = acc[mt][nt];
-        if (p.bias) x += *(const f32x4*)(p.bias + n);
-        if (p.rowbias) x += *(const f32x4*)(p.rowbias + (long long)sample * p.rowbias_ld + n);
-        if (res) {
-          bf16x4 r = *(const bf16x4*)(res + (long long)m * Nout + n);
-#pragma unroll
-          for (int v = 0; v < 4; ++v) x[v] += (float)r[v];
-        }
-        bf16x4 o;
-#pragma unroll
-        for (int v = 0; v < 4; ++v) o[v] = (bf16_t)x[v];
-        *(bf16x4*)(out + (long long)m * Nout + n) = o;
-      }
+      for (int v = 0; v < 4; ++v) o[v] = (bf16_t)x[v];
+      *(bf16x4*)(out + (long long)m * Nout + n) = o;
     }
   }
 }
