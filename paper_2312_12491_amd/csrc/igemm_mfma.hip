@@ -321,8 +321,10 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma_kernel(IgemmParams p, int m
 // Pipeline (NBUF LDS buffers, loads NBUF stages ahead): a wave reads ALL fragments of stage s into registers,
 // the block synchronises, and the buffer is immediately refilled with stage s+NBUF while the MFMAs of stage s
 // run; stages s+1 .. s+NBUF-1 are already in flight in the other buffers.  NBUF = 2 is what is built: deeper rings
-// (3 buffers with 128-row tiles, 4 with 64-row tiles) were slower on every layer of the SD-shaped net, because the
-// larger LDS footprint leaves a compute unit with fewer resident blocks.  The loads are issued from inline assembly and
+// (3 buffers with 128-row tiles, 3 to 6 with 64-row tiles) were slower on every layer of the SD-shaped net, because the
+// larger LDS footprint leaves a compute unit with fewer resident blocks; so were 256-row tiles on 8 waves (one block
+// per compute unit, weight columns fetched once for twice the rows: 121 us against 105 us on the 16384x640x5760
+// layer - the eight waves move in step, where two independent blocks overlap their load and MFMA phases).  The loads are issued from inline assembly and
 // waited for with explicit vmcnt values (every wave issues the same number per stage), because the compiler
 // would otherwise drain all outstanding loads before each LDS read.
 // ---------------------------------------------------------------------------------------------------
@@ -338,6 +340,19 @@ __device__ __forceinline__ void lds_dma16(const void* gsrc, unsigned lds_base) {
       : "=&s"(keep)
       : "s"(lds_base), "v"(gsrc)
       : "memory");
+}
+
+// waits until at most min(ahead, NBUF-1) * NLOADS of this wave's loads are outstanding (s_waitcnt takes an immediate)
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+template <int NBUF, int NLOADS> __device__ __forceinline__ void wait_stages_ahead(int ahead) {
+  if constexpr (NBUF > 1) {
+    if (ahead >= NBUF - 1) { wait_vmcnt<(NBUF - 1) * NLOADS>(); return; }
+    wait_stages_ahead<NBUF - 1, NLOADS>(ahead);
+  } else {
+    wait_vmcnt<0>();
+  }
 }
 
 template <int BM, int BN, int NBUF>
@@ -415,7 +430,8 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
 
   // Per-lane source address and validity of every A load for the cursor's position.  Inside a tap and a source
   // the address just advances by 64 channels per stage; it is rebuilt when the tap or the source changes.
-  // Past the last stage the tap index leaves the kernel window and every row reads the zero page.
+  // (The cursor is advanced once more after the last stage is issued: there the tap index leaves the kernel
+  // window and the rebuilt entries are marked invalid; they are never used.)
   const char* aptr[NLA];   // meaningless (and unused) where !okv
   bool okv[NLA];
   auto set_tap = [&]() {
@@ -442,7 +458,7 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
       lds_dma16(g, sa + (i * NW + wave) * 1024);
       aptr[i] += 128;
     }
-    const int bstep = l_stage < stage_last ? 2048 : 0;   // the weight stage is clamped to the last one
+    const int bstep = l_stage < stage_last ? 2048 : 0;   // the pointer never leaves the packed weights
 #pragma unroll
     for (int i = 0; i < NLB; ++i) {
       lds_dma16(bptr[i], sa + ABYTES + (i * NW + wave) * 1024);
@@ -475,13 +491,14 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
   }
 
 #pragma unroll
-  for (int b = 0; b < NBUF; ++b) issue(b);
+  for (int b = 0; b < NBUF; ++b)
+    if (b < nstages) issue(b);
   int buf = 0;
   for (int s = 0; s < nstages; ++s) {
-    // all but this wave's newest (NBUF-1)*NLOADS loads (stages s+1 ..) have landed, i.e. stage s has
-    constexpr int PENDING = (NBUF - 1) * NLOADS;
-    static_assert(PENDING < 64, "vmcnt is a 6-bit counter");
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (PENDING & 15) | ((PENDING >> 4) << 14));
+    // all but this wave's loads of the stages after s (NBUF-1 of them, fewer at the end: nothing is loaded past
+    // the last stage - on the short-K layers two more stages would be a third of the traffic) have landed
+    static_assert((NBUF - 1) * NLOADS < 64, "vmcnt is a 6-bit counter");
+    wait_stages_ahead<NBUF, NLOADS>(nstages - 1 - s);
     __syncthreads();                     // ... and everyone else's part of stage s too
     const unsigned char* sa = lds + buf * STAGE;
     const unsigned char* sb = sa + ABYTES;
@@ -495,7 +512,7 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
       for (int nt = 0; nt < NT; ++nt) bfr[ks][nt] = *(const bf16x8*)(sb + ((wn * NT + nt) * 2 + ks) * 1024 + lane * 16);
     }
     __syncthreads();                     // every wave holds its fragments: the buffer can be refilled
-    issue(buf);                          // stage s+NBUF
+    if (s + NBUF < nstages) issue(buf);  // stage s+NBUF
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
@@ -505,7 +522,6 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
           acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[ks][nt], af[ks][mt], acc[mt][nt], 0, 0, 0);
     buf = buf + 1 == NBUF ? 0 : buf + 1;
   }
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // the prefetches past the end must land before the block's LDS is released
   epilogue<MT, NT>(p, acc, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo, tile.split);
 }
 
