@@ -130,6 +130,9 @@ def main():
                 "launches_per_step": dr["launches"] / args.profile_steps,
                 "algorithmic_bytes_per_launch": dr["bytes"] / dr["launches"], "traffic": traffic}
 
+    # what a kernel of nothing but register-fed bf16 MFMAs reaches on this device right now (clock actually held)
+    mfma_ceiling = eng.mfma_ceiling(20000)
+
     cpu_baseline = None
     if not args.no_cpu_baseline and not args.cross_frame:   # (a cross-frame batch has no one-row sample)
         from oracle import unet as U
@@ -152,7 +155,7 @@ def main():
                                + (", cross-frame attention" if args.cross_frame else ""),
                    "timesteps": ts, "graph": not args.no_graph},
         "unet_step_ms": ms_per_step, "step_tflop": step_flops / 1e12, "mfma_util": util,
-        "peak_assumed_tflops": PEAK_BF16_TFLOPS,
+        "peak_assumed_tflops": PEAK_BF16_TFLOPS, "mfma_only_kernel_tflops": mfma_ceiling,
         "roofline": roofline, "kernel_classes": classes, "cpu_baseline": cpu_baseline,
         "context": "paper: 91.07 fps whole pipeline on one RTX 4090 (other hardware, includes VAE): not a target",
     }

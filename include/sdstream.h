@@ -166,6 +166,13 @@ int32_t sdstream_profile_read(sdstream_t* h, sdstream_profile_entry* out, int32_
 /* 0: launch kernels one by one; 1 (default): replay the step as a HIP graph captured on first use. */
 int sdstream_use_graph(sdstream_t* h, int32_t on);
 
+/* Measurement aid: the practical bf16 matrix-core ceiling of the device the handle lives on.  Runs a kernel that
+ * does nothing but dependent-free v_mfma_f32_16x16x32_bf16 chains from registers (8 waves per compute unit, `iters`
+ * rounds of 8 MFMAs per wave) on `hip_stream`, synchronises, and returns the achieved rate in *tflops_out
+ * (host).  Says what clock the chip holds under matrix load; no step of the hot path uses it.
+ * iters must be in [1, 1 << 20]. */
+int sdstream_mfma_ceiling(sdstream_t* h, int32_t iters, double* tflops_out, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -59,6 +59,7 @@ _SIGNATURES = {
                                     C.POINTER(C.c_double), C.c_void_p]),
     "sdstream_reset": (C.c_int, [C.c_void_p]),
     "sdstream_flops_per_row": (C.c_double, [C.c_void_p]),
+    "sdstream_mfma_ceiling": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.c_void_p]),
     "sdstream_profile_enable": (C.c_int, [C.c_void_p, C.c_int32]),
     "sdstream_profile_reset": (C.c_int, [C.c_void_p]),
     "sdstream_profile_read": (C.c_int32, [C.c_void_p, C.POINTER(ProfileEntry), C.c_int32]),
@@ -221,6 +222,12 @@ class Engine:
         self._check(self._l.sdstream_ssf_hard(self._h, _ptr(frame), height, width, eta, C.byref(skip), C.byref(sc),
                                               stream or None))
         return bool(skip.value), sc.value
+
+    def mfma_ceiling(self, iters: int = 20000, stream=0) -> float:
+        """Achieved TFLOP/s of a register-only bf16 MFMA kernel on this device (measurement aid)."""
+        out = C.c_double()
+        self._check(self._l.sdstream_mfma_ceiling(self._h, iters, C.byref(out), stream or None))
+        return out.value
 
     # ---- profiling
     def profile_enable(self, on: bool):

@@ -135,3 +135,6 @@ void launch_permute_bias(const float* src, float* dst, int O, int geglu_block, h
 template <typename T> void launch_convert(const float* src, void* dst, long long n, hipStream_t s);
 void launch_fill_u32(void* dst, unsigned v, long long n_words, hipStream_t s);
 void launch_copy_rows_f32(const float* src, float* dst, long long n, hipStream_t s);
+
+// blocks of 4 waves running `iters` rounds of 8 register-only MFMAs each; `sink` is never written
+void launch_mfma_ceiling(int iters, int blocks, float* sink, hipStream_t s);

@@ -1348,4 +1348,30 @@ int sdstream_use_graph(sdstream_t* h, int32_t on) {
   return SDSTREAM_OK;
 }
 
+int sdstream_mfma_ceiling(sdstream_t* h, int32_t iters, double* tflops_out, void* hip_stream) {
+  if (!h) return SDSTREAM_E_INVALID_ARG;
+  if (!tflops_out || iters < 1 || iters > (1 << 20)) return fail(h, SDSTREAM_E_INVALID_ARG, "mfma_ceiling: iters in [1, 2^20] and an output pointer are required");
+  hipStream_t s = (hipStream_t)hip_stream;
+  int dev = 0, cus = 0;
+  HIP_TRY(h, hipGetDevice(&dev));
+  HIP_TRY(h, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  const int blocks = cus * 2;   // two 4-wave blocks per compute unit: two waves per SIMD
+  float* sink = (float*)h->persist;   // only ever compared against, never written or read
+  hipEvent_t e0, e1;
+  HIP_TRY(h, hipEventCreate(&e0));
+  HIP_TRY(h, hipEventCreate(&e1));
+  launch_mfma_ceiling(iters, blocks, sink, s);   // warm-up: clocks, code load
+  HIP_TRY(h, hipEventRecord(e0, s));
+  launch_mfma_ceiling(iters, blocks, sink, s);
+  HIP_TRY(h, hipEventRecord(e1, s));
+  HIP_TRY(h, hipEventSynchronize(e1));
+  float ms = 0.f;
+  HIP_TRY(h, hipEventElapsedTime(&ms, e0, e1));
+  hipEventDestroy(e0);
+  hipEventDestroy(e1);
+  const double flops = (double)blocks * 4.0 * (double)iters * 8.0 * (2.0 * 16 * 16 * 32);
+  *tflops_out = flops / ((double)ms * 1e-3) / 1e12;
+  return SDSTREAM_OK;
+}
+
 }  // extern "C"

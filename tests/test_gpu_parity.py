@@ -190,3 +190,17 @@ def test_error_paths_leave_the_engine_usable():
     torch.cuda.synchronize()
     assert torch.isfinite(out).all()
     eng.close()
+
+
+def test_mfma_ceiling_probe_reports_a_plausible_rate():
+    # the register-only MFMA kernel cannot beat the published dense bf16 peak and should get well past half of it
+    import paper_2312_12491_amd as sd
+    wl = CONFIGS[1]
+    eng = sd.Engine(sd.config_from_dict(wl["unet"], wl["latent"], "fp32", 2, 1, 0))
+    rate = eng.mfma_ceiling(20000)
+    assert 1500.0 < rate < 2600.0, rate
+    for iters in (0, -3, (1 << 20) + 1):
+        with pytest.raises(sd.SdstreamError) as ei:
+            eng.mfma_ceiling(iters)
+        assert ei.value.code == -1
+    eng.close()
