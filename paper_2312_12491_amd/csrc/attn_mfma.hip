@@ -6,10 +6,12 @@
 // Scores are computed transposed, S^T = K Q^T, so a lane holds 16 keys of ONE query per tile: the running
 // max / sum / rescale factor are per-lane scalars and the probabilities feed the second MFMA (O^T = V^T P^T)
 // straight from registers.  The contraction order of that MFMA is a fixed permutation of the keys, applied
-// identically to P (register order) and to the V^T fragment read.
+// identically to P (register order) and to V^T (the order in which the keys of a tile are stored in LDS).
 #include "common.h"
 
 #include <stdlib.h>
+
+#include <type_traits>
 
 namespace {
 
@@ -117,6 +119,10 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
       vreg[i] = v;
     }
   };
+  // Key r of a tile sits at position vpos in a V^T row: the 8 keys a lane multiplies in one MFMA (4 consecutive
+  // from each half of a 32-key step, the order the probabilities have in registers) are then one 16-byte read.
+  const int vkey = tid & 63;
+  const int vpos = (vkey & 32) + ((vkey & 12) << 1) + ((vkey & 16) >> 2) + (vkey & 3);
   auto store_tiles = [&](int b) {
     unsigned char* Ks = smem + b * TILE;
     unsigned char* Vs = Ks + KBYTES;
@@ -134,7 +140,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
       if (c < dchunks) {
         const unsigned short* h = (const unsigned short*)&vreg[i];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) *(unsigned short*)(Vs + (c * 8 + e) * VPITCH + r * 2) = h[e];
+        for (int e = 0; e < 8; ++e) *(unsigned short*)(Vs + (c * 8 + e) * VPITCH + vpos * 2) = h[e];
       }
     }
   };
@@ -147,8 +153,10 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
   }
   store_tiles(0);
   __syncthreads();
-  int buf = 0;
-  for (int j0 = 0; j0 < Skv; j0 += BKV, buf ^= 1) {
+  // One key tile.  Only the last tile can be ragged; it gets its own copy of the body, because the compiler
+  // otherwise computes the per-key masks (about 50 vector instructions) for every tile.
+  auto key_tile = [&](auto ragged_tag, int j0, int buf) {
+    constexpr bool RAGGED = decltype(ragged_tag)::value;
     const unsigned char* Ks = smem + buf * TILE;
     const unsigned char* Vs = Ks + KBYTES;
     const bool more = j0 + BKV < Skv;
@@ -168,13 +176,20 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
           sacc[t][kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[t][ks], sacc[t][kt], 0, 0, 0);
       }
     }
+    // V^T fragments of the whole tile, requested before the softmax arithmetic that hides their latency
+    bf16x8 vfr[DT][2];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk)
+        vfr[dt][kk] = *(const bf16x8*)(Vs + (dt * 16 + li) * VPITCH + (kk * 32 + g * 8) * 2);
     bf16x8 pf[QT][2];
     float alpha[QT];
     bool rescale = false;
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
       f32x4(&s)[4] = sacc[t];
-      if (j0 + BKV > Skv) {  // ragged last tile: keys past the end must not win the max or add to the sum
+      if constexpr (RAGGED) {  // keys past the end must not win the max or add to the sum
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
@@ -215,18 +230,18 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
       }
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk) {
-        const unsigned char* row = Vs + (dt * 16 + li) * VPITCH + (kk * 32 + g * 4) * 2;
-        bf16x4 lo = *(const bf16x4*)row;
-        bf16x4 hi = *(const bf16x4*)(row + 32);
-        bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
-        for (int t = 0; t < QT; ++t) o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[t][kk], o[t][dt], 0, 0, 0);
+        for (int t = 0; t < QT; ++t)
+          o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vfr[dt][kk], pf[t][kk], o[t][dt], 0, 0, 0);
       }
     }
     // the other buffer was last read one iteration ago, before the barrier every wave has passed since
     if (more) store_tiles(buf ^ 1);
     __syncthreads();
-  }
+  };
+  int buf = 0, j0 = 0;
+  for (; j0 + BKV <= Skv; j0 += BKV, buf ^= 1) key_tile(std::false_type{}, j0, buf);
+  if (j0 < Skv) key_tile(std::true_type{}, j0, buf);
 
   bf16_t* O = (bf16_t*)p.out;
 #pragma unroll
