@@ -493,35 +493,49 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
 #pragma unroll
   for (int b = 0; b < NBUF; ++b)
     if (b < nstages) issue(b);
+
+  // Rotated loop: the MFMAs of a stage's second k-step are issued together with the fragment reads of the next
+  // stage's first k-step, so half of the LDS read latency sits in the shadow of the matrix cores.
+  bf16x8 af[2][MT], bfr[2][NT];
+  auto read_frags = [&](int ks, int buf) {
+    const unsigned char* sa = lds + buf * STAGE;
+    const unsigned char* sb = sa + ABYTES;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+      af[ks][mt] = *(const bf16x8*)(sa + a_row[mt] + (((ks * 4 + (lane >> 4)) ^ a_x[mt]) << 4));
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) bfr[ks][nt] = *(const bf16x8*)(sb + ((wn * NT + nt) * 2 + ks) * 1024 + lane * 16);
+  };
+  auto mfmas = [&](int ks) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[ks][nt], af[ks][mt], acc[mt][nt], 0, 0, 0);
+  };
+  static_assert((NBUF - 1) * NLOADS < 64, "vmcnt is a 6-bit counter");
   int buf = 0;
   for (int s = 0; s < nstages; ++s) {
     // all but this wave's loads of the stages after s (NBUF-1 of them, fewer at the end: nothing is loaded past
     // the last stage - on the short-K layers two more stages would be a third of the traffic) have landed
-    static_assert((NBUF - 1) * NLOADS < 64, "vmcnt is a 6-bit counter");
     wait_stages_ahead<NBUF, NLOADS>(nstages - 1 - s);
     __syncthreads();                     // ... and everyone else's part of stage s too
-    const unsigned char* sa = lds + buf * STAGE;
-    const unsigned char* sb = sa + ABYTES;
-    bf16x8 af[2][MT], bfr[2][NT];
+    read_frags(0, buf);
+    if (s > 0) {
+      mfmas(1);                          // second k-step of stage s-1
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        af[ks][mt] = *(const bf16x8*)(sa + a_row[mt] + (((ks * 4 + (lane >> 4)) ^ a_x[mt]) << 4));
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) bfr[ks][nt] = *(const bf16x8*)(sb + ((wn * NT + nt) * 2 + ks) * 1024 + lane * 16);
+      for (int i = 0; i < MT + NT; ++i) {   // one fragment read per two MFMAs, as long as both last
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      }
     }
+    read_frags(1, buf);
     __syncthreads();                     // every wave holds its fragments: the buffer can be refilled
     if (s + NBUF < nstages) issue(buf);  // stage s+NBUF
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[ks][nt], af[ks][mt], acc[mt][nt], 0, 0, 0);
+    mfmas(0);
     buf = buf + 1 == NBUF ? 0 : buf + 1;
   }
+  if (nstages > 0) mfmas(1);
   epilogue<MT, NT>(p, acc, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo, tile.split);
 }
 
