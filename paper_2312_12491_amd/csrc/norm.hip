@@ -352,7 +352,11 @@ bool gn_fused_plan(const GroupNormParams& p, GnFusedPlan& f) {
   f.chunks = gs * cg / 8;
   if (f.chunks > 32) return false;
   const int max_lanes = (1024 / f.chunks) & ~7;
-  int lanes = (p.HW + 7) & ~7;                    // as many pixels in parallel as a block can hold
+  // pixels in parallel: a quarter of the plane, at least 64 (measured inside the step at 16x16: 64 lanes 8.8 us,
+  // 200 lanes 10.1 us - the per-lane sums go through LDS; at 8x8: 64 lanes 6.4 us, 16 lanes 8 us)
+  int lanes = ((p.HW + 3) / 4 + 7) & ~7;
+  if (lanes < 64) lanes = 64;
+  if (lanes > ((p.HW + 7) & ~7)) lanes = (p.HW + 7) & ~7;
   if (lanes > max_lanes) lanes = max_lanes;
   if (lanes < 8) lanes = 8;
   f.lanes = lanes;
