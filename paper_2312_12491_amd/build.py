@@ -17,13 +17,18 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wno-unused-res
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
+# per-file additions.  attn_mfma: without NaNs to honour, fmaxf needs no canonicalising v_max x, x, x in front of it
+# (28 vector instructions per key tile in a kernel that is bound by them; masked scores are -3e38, never NaN)
+EXTRA = {"attn_mfma.hip": ["-fno-honor-nans"]}
+
+
 def sources():
     return sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, src[:-4] + ".o")
-    cmd = [HIPCC] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC] + FLAGS + EXTRA.get(src, []) + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:
