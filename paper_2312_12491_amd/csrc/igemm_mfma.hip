@@ -64,14 +64,56 @@ __device__ __forceinline__ TileId tile_of_block(int mtiles, int ntiles, int spli
 
 // Epilogue shared by the kernels: lane holds channels n..n+3 (n = (gnt0+nt)*16 + 4*(lane/16)) of pixel
 // m = mbase + mt*16 + lane%16 in acc[mt][nt].
-// Everything the epilogue reads (bias, time-embedding bias, residual) is requested before the first use: with a
-// load and its wait inside the (mt, nt) loops the epilogue was a chain of up to 3*MT*NT memory round trips.
+// Everything the epilogue reads (bias, time-embedding bias, residual) is requested in one go by epilogue_load,
+// before the first use: with a load and its wait inside the (mt, nt) loops the epilogue was a chain of up to
+// 3*MT*NT memory round trips.  The 64-row kernels call epilogue_load before their main loop, so that on the
+// short-K layers those round trips overlap the loop instead of following it.
+template <int MT, int NT> struct EpilogueIn {
+  f32x4 biasv[NT];       // bias; loaded values are not touched before epilogue_store (a use would wait for them)
+  f32x4 rbv[NT];         // time-embedding bias when all rows of the wave belong to one sample
+  bf16x4 rv[MT][NT];     // residual
+  bool one_sample;
+};
+
 template <int MT, int NT>
-__device__ __forceinline__ void epilogue(const IgemmParams& p, f32x4 (&acc)[MT][NT], int mbase, int gnt0, int lane,
-                                         int HWo, int split) {
+__device__ __forceinline__ void epilogue_load(const IgemmParams& p, EpilogueIn<MT, NT>& in, int mbase, int gnt0,
+                                              int lane, int HWo) {
+  in.one_sample = false;
+  if (p.splitk > 1) return;   // partial tiles take nothing in
+  const int Nout = p.epilogue == EPI_GEGLU ? p.N >> 1 : p.N;
+  const bf16_t* res = (const bf16_t*)p.residual;
+  const int ncol = (lane >> 4) * 4;
+  const int m_last = min(mbase + MT * 16, p.M) - 1;
+  in.one_sample = p.rowbias != nullptr && m_last >= mbase && mbase / HWo == m_last / HWo;   // wave-uniform
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int n = min((gnt0 + nt) * 16 + ncol, p.N - 4);   // clamped: columns past N are never stored
+    // absent terms are read from the zero page: a select on the loaded value would be a use
+    const float* bsrc = p.bias ? p.bias + n : (const float*)p.zeros;
+    const float* rsrc = in.one_sample ? p.rowbias + (long long)(mbase / HWo) * p.rowbias_ld + n : (const float*)p.zeros;
+    in.biasv[nt] = *(const f32x4*)bsrc;
+    in.rbv[nt] = *(const f32x4*)rsrc;
+  }
+  if (res && p.epilogue != EPI_GEGLU) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = max(min(mbase + mt * 16 + (lane & 15), p.M - 1), 0);
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const int n = min((gnt0 + nt) * 16 + ncol, p.N - 4);
+        in.rv[mt][nt] = *(const bf16x4*)(res + (long long)m * Nout + n);
+      }
+    }
+  }
+}
+
+template <int MT, int NT>
+__device__ __forceinline__ void epilogue_store(const IgemmParams& p, f32x4 (&acc)[MT][NT],
+                                               const EpilogueIn<MT, NT>& in, int mbase, int gnt0, int lane, int HWo,
+                                               int split) {
   const int Nout = p.epilogue == EPI_GEGLU ? p.N >> 1 : p.N;
   bf16_t* out = (bf16_t*)p.out;
-  const bf16_t* res = (const bf16_t*)p.residual;
+  const bool has_res = p.residual != nullptr;
   const int ncol = (lane >> 4) * 4;
   if (p.splitk > 1) {
 #pragma unroll
@@ -87,18 +129,9 @@ __device__ __forceinline__ void epilogue(const IgemmParams& p, f32x4 (&acc)[MT][
     }
     return;
   }
-  // per-column addends: bias, plus the time-embedding bias when all rows of this wave belong to one sample
-  const int m_last = min(mbase + MT * 16, p.M) - 1;
-  const bool one_sample = p.rowbias != nullptr && m_last >= mbase && mbase / HWo == m_last / HWo;   // wave-uniform
   f32x4 addv[NT];
 #pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    const int n = min((gnt0 + nt) * 16 + ncol, p.N - 4);   // clamped: columns past N are never stored
-    f32x4 a = {0.f, 0.f, 0.f, 0.f};
-    if (p.bias) a = *(const f32x4*)(p.bias + n);
-    if (one_sample) a += *(const f32x4*)(p.rowbias + (long long)(mbase / HWo) * p.rowbias_ld + n);
-    addv[nt] = a;
-  }
+  for (int nt = 0; nt < NT; ++nt) addv[nt] = in.biasv[nt] + in.rbv[nt];
   if (p.epilogue == EPI_GEGLU) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
@@ -118,18 +151,6 @@ __device__ __forceinline__ void epilogue(const IgemmParams& p, f32x4 (&acc)[MT][
     }
     return;
   }
-  bf16x4 rv[MT][NT];
-  if (res) {
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const int m = min(mbase + mt * 16 + (lane & 15), p.M - 1);
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        const int n = min((gnt0 + nt) * 16 + ncol, p.N - 4);
-        rv[mt][nt] = *(const bf16x4*)(res + (long long)m * Nout + n);
-      }
-    }
-  }
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     const int m = mbase + mt * 16 + (lane & 15);
@@ -140,10 +161,10 @@ __device__ __forceinline__ void epilogue(const IgemmParams& p, f32x4 (&acc)[MT][
       const int n = (gnt0 + nt) * 16 + ncol;
       if (n >= p.N) continue;
       f32x4 x = acc[mt][nt] + addv[nt];
-      if (p.rowbias && !one_sample) x += *(const f32x4*)(p.rowbias + (long long)sample * p.rowbias_ld + n);
-      if (res) {
+      if (p.rowbias && !in.one_sample) x += *(const f32x4*)(p.rowbias + (long long)sample * p.rowbias_ld + n);
+      if (has_res) {
 #pragma unroll
-        for (int v = 0; v < 4; ++v) x[v] += (float)rv[mt][nt][v];
+        for (int v = 0; v < 4; ++v) x[v] += (float)in.rv[mt][nt][v];
       }
       bf16x4 o;
 #pragma unroll
@@ -151,6 +172,14 @@ __device__ __forceinline__ void epilogue(const IgemmParams& p, f32x4 (&acc)[MT][
       *(bf16x4*)(out + (long long)m * Nout + n) = o;
     }
   }
+}
+
+template <int MT, int NT>
+__device__ __forceinline__ void epilogue(const IgemmParams& p, f32x4 (&acc)[MT][NT], int mbase, int gnt0, int lane,
+                                         int HWo, int split) {
+  EpilogueIn<MT, NT> in;
+  epilogue_load<MT, NT>(p, in, mbase, gnt0, lane, HWo);
+  epilogue_store<MT, NT>(p, acc, in, mbase, gnt0, lane, HWo, split);
 }
 
 
@@ -490,6 +519,10 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
     a_x[mt] = (r >> 1) & 7;
   }
 
+  // 64-row tiles (the short-K layers): what the epilogue reads is requested ahead of the main loop.  These
+  // loads are older than every LDS load below, so the first stage's vmcnt wait covers them.
+  EpilogueIn<MT, NT> epi_in;
+  if constexpr (BM == 64) epilogue_load<MT, NT>(p, epi_in, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo);
 #pragma unroll
   for (int b = 0; b < NBUF; ++b)
     if (b < nstages) issue(b);
@@ -536,7 +569,8 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
     buf = buf + 1 == NBUF ? 0 : buf + 1;
   }
   if (nstages > 0) mfmas(1);
-  epilogue<MT, NT>(p, acc, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo, tile.split);
+  if constexpr (BM != 64) epilogue_load<MT, NT>(p, epi_in, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo);
+  epilogue_store<MT, NT>(p, acc, epi_in, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo, tile.split);
 }
 
 // split-K finalize: sum of the partials (fp32 [splitk][M][N]) -> out with the epilogue of the main kernel
