@@ -14,6 +14,27 @@ template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return
 
 enum { EPI_NONE = 0, EPI_GEGLU = 1, EPI_SILU = 2 };
 
+// Division by a launch-time constant through one multiply-high (the round-up method of Granlund and Montgomery):
+// exact for 0 <= x < 2^31.  An integer division by a run-time value costs ~30 instructions on this target, and
+// the index set-up of a GEMM block has a dozen of them.
+struct FastDiv {
+  unsigned d, m, sh1, sh2;
+};
+inline FastDiv make_fastdiv(unsigned d) {
+  FastDiv f;
+  unsigned l = 0;
+  while ((1ull << l) < d) ++l;   // ceil(log2 d), 0 for d = 1
+  f.d = d;
+  f.m = (unsigned)(((((unsigned long long)1 << l) - d) << 32) / d + 1);
+  f.sh1 = l < 1 ? l : 1;
+  f.sh2 = l > 0 ? l - 1 : 0;
+  return f;
+}
+__device__ __forceinline__ int fast_div(int x, const FastDiv& f) {
+  const unsigned t = __umulhi(f.m, (unsigned)x);
+  return (int)((t + (((unsigned)x - t) >> f.sh1)) >> f.sh2);
+}
+
 // C[M,N] = gather(A)[M,K] * W[N,K]^T (+ bias, + per-sample bias, activation, + residual).
 // A is the implicit im2col matrix of one or two NHWC activations (channel concat): row m = (sample, oy, ox),
 // column k = tap * (C1+C2) + c with tap = ky*ksize + kx; source pixel (oy*stride + ky - pad, ox*stride + kx - pad)
@@ -38,6 +59,7 @@ struct IgemmParams {
   long long workspace_floats;
   int xcd_chunked;       // set by the MFMA launcher: block -> tile order (see tile_of_block)
   const void* zeros;     // MFMA kernel only: >= 16 readable zero bytes (source of padded / out-of-range rows)
+  FastDiv fd_hw, fd_w, fd_ct, fd_ks, fd_n;   // set by the MFMA launcher: Hout*Wout, Wout, C1+C2, ksize, N
 };
 
 #define GN_MAX_SPLIT 64

@@ -50,15 +50,15 @@ template <int I> struct IC { static constexpr int value = I; };
 // (p % 8) * (grid / 8) + p / 8 (grid padded to a multiple of 8): every XCD then owns a contiguous run of the order,
 // i.e. whole weight columns, and a weight slab is fetched into one L2 instead of eight.
 struct TileId { int mtile, ntile, split; bool valid; };
-__device__ __forceinline__ TileId tile_of_block(int mtiles, int ntiles, int splitk, int chunked) {
+__device__ __forceinline__ TileId tile_of_block(const FastDiv& mtiles, const FastDiv& ntiles, int splitk, int chunked) {
   const int per = gridDim.x >> 3;
   const int logical = chunked ? (blockIdx.x & 7) * per + (blockIdx.x >> 3) : (int)blockIdx.x;
   TileId t;
-  t.valid = logical < mtiles * ntiles * splitk;
-  t.mtile = logical % mtiles;
-  const int r = logical / mtiles;
-  t.ntile = r % ntiles;
-  t.split = r / ntiles;
+  t.valid = logical < (int)(mtiles.d * ntiles.d) * splitk;
+  const int r = fast_div(logical, mtiles);
+  t.mtile = logical - r * (int)mtiles.d;
+  t.split = fast_div(r, ntiles);
+  t.ntile = r - t.split * (int)ntiles.d;
   return t;
 }
 
@@ -84,13 +84,14 @@ __device__ __forceinline__ void epilogue_load(const IgemmParams& p, EpilogueIn<M
   const bf16_t* res = (const bf16_t*)p.residual;
   const int ncol = (lane >> 4) * 4;
   const int m_last = min(mbase + MT * 16, p.M) - 1;
-  in.one_sample = p.rowbias != nullptr && m_last >= mbase && mbase / HWo == m_last / HWo;   // wave-uniform
+  const int sample0 = fast_div(mbase, p.fd_hw);
+  in.one_sample = p.rowbias != nullptr && m_last >= mbase && sample0 == fast_div(m_last, p.fd_hw);   // wave-uniform
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     const int n = min((gnt0 + nt) * 16 + ncol, p.N - 4);   // clamped: columns past N are never stored
     // absent terms are read from the zero page: a select on the loaded value would be a use
     const float* bsrc = p.bias ? p.bias + n : (const float*)p.zeros;
-    const float* rsrc = in.one_sample ? p.rowbias + (long long)(mbase / HWo) * p.rowbias_ld + n : (const float*)p.zeros;
+    const float* rsrc = in.one_sample ? p.rowbias + (long long)sample0 * p.rowbias_ld + n : (const float*)p.zeros;
     in.biasv[nt] = *(const f32x4*)bsrc;
     in.rbv[nt] = *(const f32x4*)rsrc;
   }
@@ -155,7 +156,7 @@ __device__ __forceinline__ void epilogue_store(const IgemmParams& p, f32x4 (&acc
   for (int mt = 0; mt < MT; ++mt) {
     const int m = mbase + mt * 16 + (lane & 15);
     if (m >= p.M) continue;
-    const int sample = m / HWo;
+    const int sample = fast_div(m, p.fd_hw);
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
       const int n = (gnt0 + nt) * 16 + ncol;
@@ -184,7 +185,7 @@ __device__ __forceinline__ void epilogue(const IgemmParams& p, f32x4 (&acc)[MT][
 
 
 template <int BM, int BN, int NSETS>
-__global__ __launch_bounds__(256, 2) void igemm_mfma_kernel(IgemmParams p, int mtiles, int ksteps_total,
+__global__ __launch_bounds__(256, 2) void igemm_mfma_kernel(IgemmParams p, FastDiv mtiles, FastDiv ntiles, int ksteps_total,
                                                          int stages_per_split) {
   constexpr int WM = 2, WN = 2;
   constexpr int WTM = BM / WM, WTN = BN / WN, MT = WTM / 16, NT = WTN / 16;
@@ -196,7 +197,7 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma_kernel(IgemmParams p, int m
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave & 1, wn = wave >> 1;
-  const TileId tile = tile_of_block(mtiles, (p.N + BN - 1) / BN, p.splitk > 1 ? p.splitk : 1, p.xcd_chunked);
+  const TileId tile = tile_of_block(mtiles, ntiles, p.splitk > 1 ? p.splitk : 1, p.xcd_chunked);
   if (!tile.valid) return;  // padding block (uniform for the whole block, before any barrier)
   const int mtile = tile.mtile, ntile = tile.ntile;
   const int m0 = mtile * BM, n0 = ntile * BN;
@@ -221,9 +222,9 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma_kernel(IgemmParams p, int m
     int m = m0 + row;
     ld_ok[i] = m < p.M;
     int mm = ld_ok[i] ? m : 0;
-    int n = mm / HWo;
+    int n = fast_div(mm, p.fd_hw);
     int r = mm - n * HWo;
-    int oy = r / p.Wout, ox = r - oy * p.Wout;
+    int oy = fast_div(r, p.fd_w), ox = r - oy * p.Wout;
     ld_y[i] = oy * p.stride - pad;
     ld_x[i] = ox * p.stride - pad;
     ld_pix0[i] = (unsigned)n * (unsigned)(p.Hin * p.Win);
@@ -238,9 +239,9 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma_kernel(IgemmParams p, int m
   int l_c, l_ky, l_kx;
   {
     int kk = stage0 * 32;
-    int tap = kk / Ct;
+    int tap = fast_div(kk, p.fd_ct);
     l_c = kk - tap * Ct;
-    l_ky = tap / p.ksize;
+    l_ky = fast_div(tap, p.fd_ks);
     l_kx = tap - l_ky * p.ksize;
   }
 
@@ -385,7 +386,7 @@ template <int NBUF, int NLOADS> __device__ __forceinline__ void wait_stages_ahea
 }
 
 template <int BM, int BN, int NBUF>
-__global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mtiles, int ksteps_total,
+__global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, FastDiv mtiles, FastDiv ntiles, int ksteps_total,
                                                            int stages_per_split) {
   constexpr int WM = 2, WN = 2, NW = 4;
   constexpr int WTM = BM / WM, WTN = BN / WN, MT = WTM / 16, NT = WTN / 16;
@@ -398,7 +399,7 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave & 1, wn = wave >> 1;
-  const TileId tile = tile_of_block(mtiles, (p.N + BN - 1) / BN, p.splitk > 1 ? p.splitk : 1, p.xcd_chunked);
+  const TileId tile = tile_of_block(mtiles, ntiles, p.splitk > 1 ? p.splitk : 1, p.xcd_chunked);
   if (!tile.valid) return;  // padding block (uniform for the whole block, before any barrier)
   const int m0 = tile.mtile * BM, n0 = tile.ntile * BN;
   const int Ct = p.C1 + p.C2;
@@ -423,9 +424,9 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
     const int m = m0 + row;
     ld_ok[i] = m < p.M;
     const int mm = ld_ok[i] ? m : 0;
-    const int n = mm / HWo;
+    const int n = fast_div(mm, p.fd_hw);
     const int r = mm - n * HWo;
-    const int oy = r / p.Wout, ox = r - oy * p.Wout;
+    const int oy = fast_div(r, p.fd_w), ox = r - oy * p.Wout;
     ld_y[i] = oy * p.stride - pad;
     ld_x[i] = ox * p.stride - pad;
     ld_pix0[i] = (unsigned)n * (unsigned)(p.Hin * p.Win);
@@ -451,9 +452,9 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, int mt
   int l_c, l_ky, l_kx;
   {
     int kk = stage0 * 64;
-    int tap = kk / Ct;
+    int tap = fast_div(kk, p.fd_ct);
     l_c = kk - tap * Ct;
-    l_ky = tap / p.ksize;
+    l_ky = fast_div(tap, p.fd_ks);
     l_kx = tap - l_ky * p.ksize;
   }
 
@@ -578,13 +579,13 @@ __global__ __launch_bounds__(256) void igemm_finalize_kernel(IgemmParams p) {
   const long long idx4 = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   const long long total4 = (long long)p.M * p.N / 4;
   if (idx4 >= total4) return;
-  const long long e = idx4 * 4;
-  const int m = (int)(e / p.N), n = (int)(e - (long long)m * p.N);
+  const long long e = idx4 * 4;   // < 2^31 (checked by igemm_mfma_supported)
+  const int m = fast_div((int)e, p.fd_n), n = (int)e - m * p.N;
   // the kernel is one latency chain per thread: issue every independent load before the first add
   const long long plane = (long long)p.M * p.N;
   f32x4 add = {0.f, 0.f, 0.f, 0.f};
   if (p.bias) add = *(const f32x4*)(p.bias + n);
-  if (p.rowbias) add += *(const f32x4*)(p.rowbias + (long long)(m / (p.Hout * p.Wout)) * p.rowbias_ld + n);
+  if (p.rowbias) add += *(const f32x4*)(p.rowbias + (long long)fast_div(m, p.fd_hw) * p.rowbias_ld + n);
   bf16x4 r = {(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
   if (p.residual) r = *(const bf16x4*)((const bf16_t*)p.residual + e);
   f32x4 x = *(const f32x4*)(p.workspace + e);
@@ -612,7 +613,8 @@ template <int BM, int BN, int NSETS> void launch_cfg(const IgemmParams& p, hipSt
   const int splitk = p.splitk > 1 ? p.splitk : 1;
   const int sps = (ksteps_total + splitk - 1) / splitk;
   dim3 grid((mtiles * ntiles * splitk + 7) & ~7);
-  hipLaunchKernelGGL((igemm_mfma_kernel<BM, BN, NSETS>), grid, dim3(256), 0, s, p, mtiles, ksteps_total, sps);
+  hipLaunchKernelGGL((igemm_mfma_kernel<BM, BN, NSETS>), grid, dim3(256), 0, s, p, make_fastdiv(mtiles),
+                     make_fastdiv(ntiles), ksteps_total, sps);
   if (splitk > 1) {
     long long total4 = (long long)p.M * p.N / 4;
     hipLaunchKernelGGL(igemm_finalize_kernel, dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s, p);
@@ -632,7 +634,8 @@ template <int BM, int BN, int NBUF> void launch_dma(const IgemmParams& p, hipStr
   const int splitk = p.splitk > 1 ? p.splitk : 1;
   const int sps = (total_stages + splitk - 1) / splitk;
   dim3 grid((mtiles * ntiles * splitk + 7) & ~7);
-  hipLaunchKernelGGL((igemm_dma_kernel<BM, BN, NBUF>), grid, dim3(256), LDS, s, p, mtiles, ksteps_total, sps);
+  hipLaunchKernelGGL((igemm_dma_kernel<BM, BN, NBUF>), grid, dim3(256), LDS, s, p, make_fastdiv(mtiles),
+                     make_fastdiv(ntiles), ksteps_total, sps);
   if (splitk > 1) {
     long long total4 = (long long)p.M * p.N / 4;
     hipLaunchKernelGGL(igemm_finalize_kernel, dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s, p);
@@ -725,6 +728,7 @@ bool igemm_mfma_supported(const IgemmParams& p) {
   const long long cmax = p.C1 > p.C2 ? p.C1 : p.C2;
   if (samples * p.Hin * p.Win * cmax * 2 >= (1LL << 32)) return false;
   if ((long long)p.N * p.K * 2 >= (1LL << 32)) return false;
+  if ((long long)p.M * p.N >= (1LL << 31)) return false;   // output element indices are divided as 31-bit values
   return true;
 }
 
@@ -738,6 +742,11 @@ void launch_igemm_mfma(const IgemmParams& p0, hipStream_t s) {
     p.splitk = (stages + sps - 1) / sps;
   }
   p.xcd_chunked = (long long)p.N * p.K > (long long)p.M * (p.C1 + p.C2) ? 1 : 0;
+  p.fd_hw = make_fastdiv((unsigned)(p.Hout * p.Wout));
+  p.fd_w = make_fastdiv((unsigned)p.Wout);
+  p.fd_ct = make_fastdiv((unsigned)(p.C1 + p.C2));
+  p.fd_ks = make_fastdiv((unsigned)p.ksize);
+  p.fd_n = make_fastdiv((unsigned)p.N);
   if (c.bn == 160) launch_bn<160>(p, c.variant, s);
   else if (c.bn == 128) launch_bn<128>(p, c.variant, s);
   else launch_bn<64>(p, c.variant, s);

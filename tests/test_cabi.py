@@ -76,3 +76,27 @@ def test_ssf_decide_hard_matches_the_oracle():
     assert ssf_decide_hard(0, 0, 5, 0.5) == (False, 0.0)
     assert ssf_decide_hard(25, 25, 25, 0.98) == (True, 1.0)
     assert ssf_decide_hard(25, 25, 25, 1.0) == (False, 1.0)
+
+
+def test_multiply_high_division_is_exact():
+    # the GEMM kernels divide block and pixel indices by launch-time constants with one multiply-high
+    # (round-up method): same arithmetic as make_fastdiv / fast_div in csrc/common.h, checked against // here
+    import random
+
+    def make(d):
+        l = 0 if d == 1 else (d - 1).bit_length()
+        return ((((1 << l) - d) << 32) // d + 1, min(l, 1), max(l - 1, 0))
+
+    def fdiv(x, f):
+        m, sh1, sh2 = f
+        t = (m * x) >> 32
+        return ((t + (((x - t) & 0xFFFFFFFF) >> sh1)) & 0xFFFFFFFF) >> sh2
+
+    rng = random.Random(7)
+    for d in list(range(1, 700)) + [4095, 4096, 4097, 9216, 16384, 65537, 147456, (1 << 31) - 1]:
+        f = make(d)
+        assert f[0] < (1 << 32)
+        xs = [0, 1, d - 1, d, d + 1, 2 * d - 1, (1 << 31) - 1, (1 << 31) - d] + [rng.randrange(1 << 31) for _ in range(50)]
+        for x in xs:
+            if 0 <= x < (1 << 31):
+                assert fdiv(x, f) == x // d, (d, x)
