@@ -102,6 +102,18 @@ __device__ __forceinline__ bf16x8 gn_load8(const GroupNormParams& p, long long p
   return *(const bf16x8*)src;
 }
 
+// group of channel c0 + e for e = 0..7 with one division instead of eight (a run-time integer division is ~30
+// instructions; the kernels around here are a few microseconds long)
+struct GroupWalk {
+  int g, r, cg;
+  __device__ __forceinline__ GroupWalk(int c0, int cg_) : g(c0 / cg_), r(c0 - (c0 / cg_) * cg_), cg(cg_) {}
+  __device__ __forceinline__ int next() {   // group of the current channel, then advance by one channel
+    const int cur = g;
+    if (++r == cg) { r = 0; ++g; }
+    return cur;
+  }
+};
+
 // Both passes are latency chains, not streams (their time barely changes between 1 and 4 samples), so they are
 // built to be short: blocks of up to 512 threads (more for rows wider than 512 chunks) so that a thread touches a
 // few pixels with all its loads in flight at once, and reductions in three parallel steps (pixel lanes -> channel totals -> 8 threads per group
@@ -208,9 +220,10 @@ __global__ __launch_bounds__(1024) void gn_apply_bf16_kernel(GroupNormParams p, 
   }
   __syncthreads();
   float sc[8], sh[8];
+  GroupWalk walk(chunk * 8, cg);
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    const int c = chunk * 8 + e, g = c / cg;
+    const int c = chunk * 8 + e, g = walk.next();
     const float rs = sm[g * 2 + 1] * p.gamma[c];
     sc[e] = rs;
     sh[e] = p.beta[c] - sm[g * 2] * rs;
@@ -316,9 +329,10 @@ __global__ __launch_bounds__(1024) void gn_fused_bf16_kernel(GroupNormParams p, 
   }
   __syncthreads();
   float sc[8], sh[8];
+  GroupWalk walk(chunk * 8, cg);
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    const int cl = chunk * 8 + e, g = cl / cg;
+    const int cl = chunk * 8 + e, g = walk.next();
     const float rs = mr[g * 2 + 1] * (e < 4 ? ga0[e & 3] : ga1[e & 3]);
     sc[e] = rs;
     sh[e] = (e < 4 ? be0[e & 3] : be1[e & 3]) - mr[g * 2] * rs;
