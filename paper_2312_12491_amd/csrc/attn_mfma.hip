@@ -99,45 +99,58 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
   constexpr int VSLOTS = (DT * 2 + 3) / 4;
   uint4 kreg[KSLOTS], vreg[VSLOTS];
   const int nkchunks = BKV * dchunks;
+  // Everything about a slot that does not depend on the key tile is worked out once: the loaders run per tile and
+  // were, with their index arithmetic, longer than the tile's MFMA and softmax work at one query tile per wave.
+  const bf16_t* kptr[KSLOTS];   // row r, chunk c of key tile 0
+  int krow[KSLOTS], klds[KSLOTS];   // row (BKV when the slot is unused: never below Skv - j0), LDS byte offset
+#pragma unroll
+  for (int i = 0; i < KSLOTS; ++i) {
+    const int ch = tid + i * 256;
+    const int r = ch / dchunks, c = ch - r * dchunks;
+    const bool used = ch < nkchunks;
+    krow[i] = used ? r : (1 << 30);
+    klds[i] = r * KPITCH + c * 16;
+    kptr[i] = K + kvoff + (long long)r * p.ldk + c0 + c * 8;
+  }
+  const int vkey = tid & 63;
+  const bf16_t* vptr[VSLOTS];
+  bool vuse[VSLOTS];
+#pragma unroll
+  for (int i = 0; i < VSLOTS; ++i) {
+    const int c = (tid >> 6) + 4 * i;
+    vuse[i] = c < dchunks;
+    vptr[i] = V + kvoff + (long long)vkey * p.ldv + c0 + c * 8;
+  }
 
   auto load_tiles = [&](int j0) {
+    const long long koff = (long long)j0 * p.ldk, voff = (long long)j0 * p.ldv;
+    const int left = Skv - j0;   // keys from j0 on
 #pragma unroll
     for (int i = 0; i < KSLOTS; ++i) {
-      int ch = tid + i * 256;
       uint4 v = make_uint4(0, 0, 0, 0);
-      if (ch < nkchunks) {
-        int r = ch / dchunks, c = ch - r * dchunks;
-        if (j0 + r < Skv) v = *(const uint4*)(K + kvoff + (long long)(j0 + r) * p.ldk + c0 + c * 8);
-      }
+      if (krow[i] < left) v = *(const uint4*)(kptr[i] + koff);
       kreg[i] = v;
     }
 #pragma unroll
     for (int i = 0; i < VSLOTS; ++i) {
-      int c = (tid >> 6) + 4 * i, r = tid & 63;
       uint4 v = make_uint4(0, 0, 0, 0);
-      if (c < dchunks && j0 + r < Skv) v = *(const uint4*)(V + kvoff + (long long)(j0 + r) * p.ldv + c0 + c * 8);
+      if (vuse[i] && vkey < left) v = *(const uint4*)(vptr[i] + voff);
       vreg[i] = v;
     }
   };
   // Key r of a tile sits at position vpos in a V^T row: the 8 keys a lane multiplies in one MFMA (4 consecutive
   // from each half of a 32-key step, the order the probabilities have in registers) are then one 16-byte read.
-  const int vkey = tid & 63;
   const int vpos = (vkey & 32) + ((vkey & 12) << 1) + ((vkey & 16) >> 2) + (vkey & 3);
   auto store_tiles = [&](int b) {
     unsigned char* Ks = smem + b * TILE;
     unsigned char* Vs = Ks + KBYTES;
 #pragma unroll
-    for (int i = 0; i < KSLOTS; ++i) {
-      int ch = tid + i * 256;
-      if (ch < nkchunks) {
-        int r = ch / dchunks, c = ch - r * dchunks;
-        *(uint4*)(Ks + r * KPITCH + c * 16) = kreg[i];
-      }
-    }
+    for (int i = 0; i < KSLOTS; ++i)
+      if (krow[i] < BKV) *(uint4*)(Ks + klds[i]) = kreg[i];
 #pragma unroll
     for (int i = 0; i < VSLOTS; ++i) {
-      int c = (tid >> 6) + 4 * i, r = tid & 63;
-      if (c < dchunks) {
+      const int c = (tid >> 6) + 4 * i;
+      if (vuse[i]) {
         const unsigned short* h = (const unsigned short*)&vreg[i];
 #pragma unroll
         for (int e = 0; e < 8; ++e) *(unsigned short*)(Vs + (c * 8 + e) * VPITCH + vpos * 2) = h[e];
@@ -176,13 +189,17 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
           sacc[t][kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[t][ks], sacc[t][kt], 0, 0, 0);
       }
     }
-    // V^T fragments of the whole tile, requested before the softmax arithmetic that hides their latency
-    bf16x8 vfr[DT][2];
+    // V^T fragments of the whole tile, requested before the softmax arithmetic that hides their latency - where
+    // the registers are there (DT * QT <= 12: not d = 64 with 4 query tiles, not d = 160 with 2)
+    constexpr bool VPRE = DT * QT <= 12;
+    bf16x8 vfr[VPRE ? DT : 1][2];
+    if constexpr (VPRE) {
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
+      for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-      for (int kk = 0; kk < 2; ++kk)
-        vfr[dt][kk] = *(const bf16x8*)(Vs + (dt * 16 + li) * VPITCH + (kk * 32 + g * 8) * 2);
+        for (int kk = 0; kk < 2; ++kk)
+          vfr[dt][kk] = *(const bf16x8*)(Vs + (dt * 16 + li) * VPITCH + (kk * 32 + g * 8) * 2);
+    }
     bf16x8 pf[QT][2];
     float alpha[QT];
     bool rescale = false;
@@ -230,9 +247,12 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
       }
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk) {
+        bf16x8 vf;
+        if constexpr (VPRE) vf = vfr[dt][kk];
+        else vf = *(const bf16x8*)(Vs + (dt * 16 + li) * VPITCH + (kk * 32 + g * 8) * 2);
 #pragma unroll
         for (int t = 0; t < QT; ++t)
-          o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vfr[dt][kk], pf[t][kk], o[t][dt], 0, 0, 0);
+          o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[t][kk], o[t][dt], 0, 0, 0);
       }
     }
     // the other buffer was last read one iteration ago, before the barrier every wave has passed since
