@@ -645,8 +645,11 @@ template <int BM, int BN, int NBUF> void launch_dma(const IgemmParams& p, hipStr
 struct Choice { int variant, bn, splitk; };  // variant 0: 32-deep stages, weights through registers (any C % 32 == 0);
                                              // 1: direct-to-LDS kernel with 128-row tiles, 2: with 64-row tiles
 
-// Tile / kernel / split-K selection, from per-layer timings of the SD-shaped net on MI355X: long K or grids of
-// several rounds take full 128-row tiles, the rest 64-row tiles; grids below the chip size split K.
+// Tile / kernel / split-K selection, from per-layer timings of the SD-shaped net on MI355X (256 compute units).
+// What the timings say: a layer runs best with about one 128-row tile per compute unit - 256 blocks beat 512 blocks
+// of half the size or half the K range (fewer fetches of each operand across L2 -> LDS, fewer partial tiles) -
+// until a block's share of K passes ~100 stages, where a second block per unit pays again.  Layers with fewer tiles
+// than that split K if K is long, and otherwise fall back to 64-row tiles.
 Choice choose(const IgemmParams& p) {
   Choice c;
   const bool k64 = p.C1 % 64 == 0 && p.C2 % 64 == 0;
@@ -659,37 +662,43 @@ Choice choose(const IgemmParams& p) {
   const bool may_split = p.epilogue == EPI_NONE && p.workspace != nullptr;
   const long long mn = (long long)p.M * p.N;
   auto blocks = [&](int bm, int bn) { return ((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn); };
+  // K splits for a grid of nb tiles: up to one block per compute unit, two where a block would walk > 100 stages
+  auto split_for = [&](int nb) {
+    int k = nb >= 200 ? 1 : (256 + nb / 2) / nb;
+    if (stages / k > 100) k *= 2;
+    const int most = stages / 8 > 1 ? stages / 8 : 1;
+    return k < most ? k : most;
+  };
   // 128-row tiles: of the widths that divide N, the one that fills whole rounds of 512 resident blocks best
   int bn6 = bn0;
   if (!geglu && p.N % 160 == 0 && p.N % 128 == 0) {
     auto fill = [&](int bn) { const int nb = blocks(128, bn); return (double)nb / (double)(((nb + 511) / 512) * 512); };
     if (fill(128) > fill(160) + 1e-3) bn6 = 128;
   }
-  int nb128 = blocks(128, bn6);
   int sk = 1;
-  if ((stages >= 64 && (long long)stages * nb128 >= 8000) || (nb128 >= 400 && stages >= 5 && p.M >= 4096)) {
-    // long K or a grid of several rounds: full tiles, split K when the grid is below the chip size
+  if (blocks(128, bn6) >= 200 && stages >= 5) {
     c.variant = 1;
-    c.bn = nb128 >= 400 ? bn6 : bn0;
-    nb128 = blocks(128, c.bn);
-    if (nb128 < 400) sk = (512 + nb128 / 2) / nb128 < stages / 8 ? (512 + nb128 / 2) / nb128 : stages / 8;
-  } else {
-    c.variant = 2;
-    if (stages >= 32) {
-      const int nb = blocks(64, c.bn);
-      if (nb < 512) sk = 512 / nb < stages / 8 ? 512 / nb : stages / 8;
-      // a split grid does better with full tiles (half as many blocks, each twice the work per weight byte),
-      // as long as enough blocks remain
-      if (sk > 1 && may_split && blocks(128, c.bn) * sk >= 150) c.variant = 1;
+    c.bn = bn6;
+    sk = split_for(blocks(128, bn6));
+  } else if (stages >= 32) {
+    // long K, few tiles: split K; full tiles as long as enough blocks remain
+    const int s1 = split_for(blocks(128, bn0));
+    if (may_split && blocks(128, bn0) * s1 >= 150) {
+      c.variant = 1;
+      sk = s1;
     } else {
-      // short K (most 1x1 layers): shrink the tile rather than split K
-      if (blocks(64, c.bn) < 512) {
-        if (!geglu && p.N % 128 == 0 && blocks(64, 128) >= 400) c.bn = 128;
-        else if (p.N % 64 == 0) c.bn = 64;
-      }
-      const int nb = blocks(64, c.bn);
-      if (nb < 192 && stages >= 16) sk = 512 / nb < stages / 8 ? 512 / nb : stages / 8;
+      c.variant = 2;
+      sk = split_for(blocks(64, bn0));
     }
+  } else {
+    // short K, few tiles (most 1x1 layers of the deeper levels): narrower 64-row tiles rather than a split
+    c.variant = 2;
+    if (blocks(64, c.bn) < 256) {
+      if (!geglu && p.N % 128 == 0 && blocks(64, 128) >= 200) c.bn = 128;
+      else if (p.N % 64 == 0) c.bn = 64;
+    }
+    const int nb = blocks(64, c.bn);
+    if (nb < 64 && stages >= 16) sk = split_for(nb);
   }
   if (!may_split) sk = 1;
   if ((long long)sk * mn > p.workspace_floats) sk = (int)(p.workspace_floats / mn);
