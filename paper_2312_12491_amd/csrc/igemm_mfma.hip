@@ -669,10 +669,10 @@ Choice choose(const IgemmParams& p) {
     const int most = stages / 8 > 1 ? stages / 8 : 1;
     return k < most ? k : most;
   };
-  // 128-row tiles: of the widths that divide N, the one that fills whole rounds of 512 resident blocks best
+  // 128-row tiles: of the widths that divide N, the one that fills whole rounds of one block per compute unit best
   int bn6 = bn0;
   if (!geglu && p.N % 160 == 0 && p.N % 128 == 0) {
-    auto fill = [&](int bn) { const int nb = blocks(128, bn); return (double)nb / (double)(((nb + 511) / 512) * 512); };
+    auto fill = [&](int bn) { const int nb = blocks(128, bn); return (double)nb / (double)(((nb + 255) / 256) * 256); };
     if (fill(128) > fill(160) + 1e-3) bn6 = 128;
   }
   int sk = 1;
