@@ -22,7 +22,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 # (config, cfg_mode) -> measured memory traffic in bytes per implicit-GEMM layer launch (profiles/igemm_config3_hbm_traffic.txt)
-TRAFFIC_BYTES_PER_LAUNCH = {(3, 0): 70.4e6}
+TRAFFIC_BYTES_PER_LAUNCH = {(3, 0): 66.8e6}
 
 
 def main():
