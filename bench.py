@@ -21,8 +21,28 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
-# (config, cfg_mode) -> measured memory traffic in bytes per implicit-GEMM layer launch (profiles/igemm_config3_hbm_traffic.txt)
-TRAFFIC_BYTES_PER_LAUNCH = {(3, 0): 66.8e6}
+
+
+def measured_traffic(config: int, mode: int, launches_per_step: float):
+    """HBM bytes per launch of the implicit-GEMM class from the rocprofv3 --pmc summary under profiles/ (FETCH_SIZE
+    and WRITE_SIZE passes, scaled by what the same counters read for a plain copy).  The summary carries one line
+    `bench: key=value ...` naming the workload and the launch count it was taken on; a summary of another workload,
+    or of a build with a different number of launches per step (i.e. stale), gives None."""
+    path = os.path.join(ROOT, "profiles", f"igemm_config{config}_hbm_traffic.txt")
+    try:
+        lines = open(path).read().splitlines()
+    except OSError:
+        return None
+    for ln in lines:
+        if ln.startswith("# bench:"):
+            kv = dict(item.split("=", 1) for item in ln[len("# bench:"):].split())
+            try:
+                if int(kv["config"]) == config and int(kv["mode"]) == mode and \
+                        abs(float(kv["launches_per_step"]) - launches_per_step) < 0.5:
+                    return float(kv["traffic_bytes_per_launch"])
+            except (KeyError, ValueError):
+                return None
+    return None
 
 
 def main():
@@ -112,6 +132,9 @@ def main():
                              ms_per_step=r["ms"] / args.profile_steps,
                              tflops=r["flops"] / (r["ms"] * 1e-3) / 1e12 if r["ms"] > 0 else 0.0,
                              gbs=r["bytes"] / (r["ms"] * 1e-3) / 1e9 if r["ms"] > 0 else 0.0)
+    for name, c in classes.items():   # fraction of the roofline that bounds the class (event time, dispatch gap included)
+        c["frac_of_peak"] = c["tflops"] / PEAK_BF16_TFLOPS if name.endswith("mfma") else c["gbs"] / PEAK_HBM_GBS
+        c["bound"] = "mfma" if name.endswith("mfma") else "hbm"
     # An event pair around an eager launch also spans a dispatch gap.  The same kernels replayed as a graph take
     # ms_per_step in total, so the gap per bracketed launch is what makes the bracketed times add up to that.
     n_pairs = sum(c["launches_per_step"] for c in classes.values())
@@ -123,7 +146,8 @@ def main():
     achieved = dr["flops"] / dr["launches"] / (launch_us * 1e-6) / 1e12
     # HBM-side bytes per launch of this kernel class, from the two rocprofv3 --pmc passes summarised under profiles/
     # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 256 MiB copy); only valid for the workload they were taken on
-    traffic = TRAFFIC_BYTES_PER_LAUNCH.get((args.config, mode)) if dom == "igemm_mfma" and not args.cross_frame else None
+    traffic = measured_traffic(args.config, mode, dr["launches"] / args.profile_steps) \
+        if dom == "igemm_mfma" and not args.cross_frame else None
     roofline = {"kernel": dom, "bound": "mfma" if dom.endswith("mfma") else "alu",
                 "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                 "avg_launch_us": launch_us, "event_pair_overhead_us": pair_us,
@@ -142,7 +166,7 @@ def main():
         t1 = time.perf_counter()
         net(xs, [ts[0]], torch.as_tensor(inp["context"]))
         t_row = time.perf_counter() - t1
-        cpu_baseline = {"value": 1.0 / (t_row * rows / S), "unit": "frames/s", "cores": torch.get_num_threads(),
+        cpu_baseline = {"value": 1.0 / (t_row * rows / S), "unit": "frames/s", "cores": min(torch.get_num_threads(), len(os.sched_getaffinity(0))),
                         "kind": "oracle", "sample": f"one U-Net row of the {rows}-row step (float64), "
                         f"{t_row:.1f} s, scaled to {rows} rows; the elementwise tail is negligible"}
 

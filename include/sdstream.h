@@ -10,7 +10,9 @@
  *
  * Conventions
  *   - Every function returns SDSTREAM_OK (0) or a negative SDSTREAM_E_* code; nothing throws or aborts.  After a
- *     failure sdstream_last_error() gives a message and the handle's queue state is unchanged.
+ *     failure sdstream_last_error() gives a message.  A call that fails its argument checks leaves the handle as
+ *     it was; sdstream_step with a new timestep list clears the queue before it launches anything, so a HIP
+ *     error reported after that point leaves an empty queue.
  *   - "host" / "device" on a pointer says where the memory lives.  The library never keeps, frees or writes a
  *     caller's input pointer after the call returns (device inputs must stay valid until the stream has run).
  *   - Tensors at the boundary are float32, latents NCHW [.,C,H,W], contexts row-major [L,D].
@@ -90,7 +92,8 @@ int sdstream_load_weights(sdstream_t* h, const void* host_blob, size_t bytes);
  * Resets the queue. */
 int sdstream_set_schedule(sdstream_t* h, const float* alphas_cumprod);
 
-/* The pre-sampled noise of the appendix: host, [n][S][C][H][W], fixed for the session.  Resets the queue. */
+/* The pre-sampled noise of the appendix: host, [n][S][C][H][W], fixed for the session.  Waits for all work on
+ * the device, copies, then does what sdstream_reset does (queue and reference latents zeroed). */
 int sdstream_set_noise(sdstream_t* h, const float* host_noise);
 
 /* One pass of Sec. 3.1: takes one clean latent per stream, advances every queued latent one denoising step
@@ -141,7 +144,14 @@ int sdstream_ssf_decide_hard(uint64_t dot, uint64_t n_t, uint64_t n_ref, double 
 int sdstream_ssf_hard(sdstream_t* h, const uint8_t* frame, int32_t height, int32_t width, double eta, int32_t* skip,
                       double* similarity, void* hip_stream);
 
-/* Clears the queue, the reference latents, the filter's reference frame and the warm-up counter. */
+/* Run statistics of the similarity filters (either kind) since create / the last reset, for the duty-cycle
+ * comparison of Sec. 3.4 and Table 3: frames seen, frames let through (= denoising steps that still run; the
+ * paper's power figure follows this share), and the longest run of consecutive skips (how long the output stayed
+ * stuck).  Host pointers, each may be NULL. */
+int sdstream_ssf_run_stats(const sdstream_t* h, int64_t* frames, int64_t* processed, int64_t* longest_skip_run);
+
+/* Waits for the device, then zeroes the queue and the reference latents and clears the filter's reference frame,
+ * the filter's run statistics and the warm-up counter. */
 int sdstream_reset(sdstream_t* h);
 
 /* Multiply-add work of one U-Net row as 2*M*N*K summed over every convolution, linear layer and attention

@@ -57,6 +57,8 @@ _SIGNATURES = {
     "sdstream_ssf_decide_hard": (C.c_int, [C.c_uint64, C.c_uint64, C.c_uint64, C.c_double, C.POINTER(C.c_double)]),
     "sdstream_ssf_hard": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.POINTER(C.c_int32),
                                     C.POINTER(C.c_double), C.c_void_p]),
+    "sdstream_ssf_run_stats": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64),
+                                         C.POINTER(C.c_int64)]),
     "sdstream_reset": (C.c_int, [C.c_void_p]),
     "sdstream_flops_per_row": (C.c_double, [C.c_void_p]),
     "sdstream_mfma_ceiling": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.c_void_p]),
@@ -222,6 +224,12 @@ class Engine:
         self._check(self._l.sdstream_ssf_hard(self._h, _ptr(frame), height, width, eta, C.byref(skip), C.byref(sc),
                                               stream or None))
         return bool(skip.value), sc.value
+
+    def ssf_run_stats(self):
+        """(frames seen, frames let through, longest run of consecutive skips) since the last reset."""
+        f, p, l = C.c_int64(), C.c_int64(), C.c_int64()
+        self._check(self._l.sdstream_ssf_run_stats(self._h, C.byref(f), C.byref(p), C.byref(l)))
+        return f.value, p.value, l.value
 
     def mfma_ceiling(self, iters: int = 20000, stream=0) -> float:
         """Achieved TFLOP/s of a register-only bf16 MFMA kernel on this device (measurement aid)."""

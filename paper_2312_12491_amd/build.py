@@ -15,6 +15,10 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wno-unused-result", "-Wno-unused-value",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+# SDSTREAM_DEVHOOKS=1 in the environment of the BUILD compiles in the environment-variable switches used for kernel
+# sweeps (SDSTREAM_TUNE, SDSTREAM_ATTN_QT, SDSTREAM_NO_MFMA, SDSTREAM_PROFILE_OPS); the normal library reads none.
+if os.environ.get("SDSTREAM_DEVHOOKS") == "1":
+    FLAGS.append("-DSDSTREAM_DEVHOOKS")
 
 
 # per-file additions.  attn_mfma: without NaNs to honour, fmaxf needs no canonicalising v_max x, x, x in front of it

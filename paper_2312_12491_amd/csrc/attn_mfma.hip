@@ -297,7 +297,11 @@ template <int DK, int DT, int QT, bool ONES> void launch_qt(const AttnParams& p,
 
 // more query tiles per wave amortise the K / V fragment reads; fewer keep small problems spread over the chip
 template <int DK, int DT, bool ONES> void launch_cfg(const AttnParams& p, hipStream_t s) {
+#ifdef SDSTREAM_DEVHOOKS
   static const int force = getenv("SDSTREAM_ATTN_QT") ? atoi(getenv("SDSTREAM_ATTN_QT")) : 0;
+#else
+  constexpr int force = 0;
+#endif
   auto blocks = [&](int qt) { return (long long)((p.Sq + 64 * qt - 1) / (64 * qt)) * p.heads * p.samples; };
   int qt = 1;
   if (blocks(2) >= 512) qt = 2;

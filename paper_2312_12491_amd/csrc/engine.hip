@@ -13,9 +13,11 @@
 #include <string>
 #include <vector>
 
-namespace {
+// message of the last failed call that had no handle to keep it in (sdstream_last_error(NULL)); per thread
+thread_local std::string g_sdstream_create_error;
+#define g_create_error g_sdstream_create_error
 
-thread_local std::string g_create_error;
+namespace {
 
 // ------------------------------------------------------------------------------------------------
 // plan-time interval allocator (first fit, coalescing).  Offsets are in bytes for ONE sample; the
@@ -159,7 +161,7 @@ struct sdstream {
   size_t off_x[2] = {0, 0}, off_r[2] = {0, 0}, off_eps = 0, off_noise = 0, off_ab = 0;
   size_t off_unet_x = 0;  // fp32 input batch for unet_forward
   size_t off_zeros = 0;   // 256 bytes that stay zero
-  size_t off_splitk = 0;  // fp32 [M][N] accumulator of split-K GEMMs, zero between launches
+  size_t off_splitk = 0;  // fp32 [splits][M][N] partial tiles of a split-K GEMM (every launch overwrites what it reads back)
   double flops_per_row = 0;
 
   // state
@@ -180,6 +182,8 @@ struct sdstream {
   long long ssf_n = 0;
   int ssf_ref = -1;
   uint64_t ssf_ref_norm = 0;
+  // run statistics of the filter since the last reset (Sec. 3.4: the share of frames that still reach the U-Net)
+  long long ssf_frames = 0, ssf_processed = 0, ssf_skip_run = 0, ssf_longest_skip_run = 0;
 
   // graph
   bool graph_enabled = true;
@@ -735,6 +739,17 @@ void reset_state(sdstream* h) {
   h->calls = 0;
   h->ssf_ref = -1;
   h->ssf_ref_norm = 0;
+  h->ssf_frames = h->ssf_processed = h->ssf_skip_run = h->ssf_longest_skip_run = 0;
+}
+
+void ssf_count(sdstream* h, bool skipped) {
+  h->ssf_frames++;
+  if (skipped) {
+    if (++h->ssf_skip_run > h->ssf_longest_skip_run) h->ssf_longest_skip_run = h->ssf_skip_run;
+  } else {
+    h->ssf_processed++;
+    h->ssf_skip_run = 0;
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -933,7 +948,10 @@ int sdstream_create(const sdstream_config* cfg, sdstream_t** out) {
   if (!h) return fail(nullptr, SDSTREAM_E_NOMEM, "out of host memory");
   h->cfg = *cfg;
   h->elt = cfg->dtype == 1 ? 2 : 4;
-  h->use_mfma = cfg->dtype == 1 && getenv("SDSTREAM_NO_MFMA") == nullptr;
+  h->use_mfma = cfg->dtype == 1;
+#ifdef SDSTREAM_DEVHOOKS
+  if (getenv("SDSTREAM_NO_MFMA")) h->use_mfma = false;   // development build only: bf16 storage on the vector-ALU kernels
+#endif
   h->E = cfg->in_channels * cfg->latent_h * cfg->latent_w;
   h->max_batch = rows_for_mode(*cfg);
   memset(h->prof, 0, sizeof h->prof);
@@ -1062,10 +1080,11 @@ int sdstream_set_schedule(sdstream_t* h, const float* alphas_cumprod) {
 int sdstream_set_noise(sdstream_t* h, const float* host_noise) {
   if (!h || !host_noise) return h ? fail(h, SDSTREAM_E_INVALID_ARG, "null noise") : SDSTREAM_E_INVALID_ARG;
   size_t bytes = (size_t)h->cfg.n_denoise * h->cfg.n_streams * h->E * 4;
+  // drains every stream of the device first: a step still in flight reads the cache
+  HIP_TRY(h, hipDeviceSynchronize());
   HIP_TRY(h, hipMemcpy(h->persist + h->off_noise, host_noise, bytes, hipMemcpyHostToDevice));
   h->have_noise = true;
-  reset_state(h);
-  return SDSTREAM_OK;
+  return sdstream_reset(h);
 }
 
 int sdstream_reset(sdstream_t* h) {
@@ -1258,6 +1277,7 @@ int sdstream_ssf(sdstream_t* h, const uint8_t* frame, int32_t height, int32_t wi
     h->ssf_ref = spare;
     h->ssf_ref_norm = nt;
   }
+  ssf_count(h, sk != 0);
   *skip = sk;
   if (prob) *prob = p;
   return SDSTREAM_OK;
@@ -1278,8 +1298,17 @@ int sdstream_ssf_hard(sdstream_t* h, const uint8_t* frame, int32_t height, int32
     h->ssf_ref = spare;
     h->ssf_ref_norm = nt;
   }
+  ssf_count(h, sk != 0);
   *skip = sk;
   if (similarity) *similarity = sc;
+  return SDSTREAM_OK;
+}
+
+int sdstream_ssf_run_stats(const sdstream_t* h, int64_t* frames, int64_t* processed, int64_t* longest_skip_run) {
+  if (!h) return SDSTREAM_E_INVALID_ARG;
+  if (frames) *frames = h->ssf_frames;
+  if (processed) *processed = h->ssf_processed;
+  if (longest_skip_run) *longest_skip_run = h->ssf_longest_skip_run;
   return SDSTREAM_OK;
 }
 
@@ -1294,7 +1323,9 @@ static int prof_drain(sdstream* h) {
   for (auto& r : h->prof_pending) {
     float ms = 0.f;
     hipEventElapsedTime(&ms, r.a, r.b);
-    if (r.op >= 0 && getenv("SDSTREAM_PROFILE_OPS")) {
+#ifdef SDSTREAM_DEVHOOKS
+    static const bool print_ops = getenv("SDSTREAM_PROFILE_OPS") != nullptr;
+    if (r.op >= 0 && print_ops) {
       const Op& op = h->ops[r.op];
       if (op.kind == OP_IGEMM)
         fprintf(stderr, "op %3d %-11s M=%d N=%d K=%d ks=%d st=%d up=%d epi=%d res=%d  %.1f us  %.1f TF/s\n", r.op,
@@ -1307,6 +1338,7 @@ static int prof_drain(sdstream* h) {
         fprintf(stderr, "op %3d %-11s rows=%d  %.1f us  %.1f GB/s\n", r.op, kProfNames[r.cls],
                 r.N * op.rows_per_sample, ms * 1e3, r.bytes / (ms * 1e-3) / 1e9);
     }
+#endif
     sdstream_profile_entry& e = h->prof[r.cls];
     e.launches += 1;
     e.ms += ms;

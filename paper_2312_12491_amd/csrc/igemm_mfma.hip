@@ -703,7 +703,9 @@ Choice choose(const IgemmParams& p) {
   if (!may_split) sk = 1;
   if ((long long)sk * mn > p.workspace_floats) sk = (int)(p.workspace_floats / mn);
   c.splitk = sk > 1 ? sk : 1;
-  if (const char* t = getenv("SDSTREAM_TUNE")) {  // "variant,bn,splitk" for sweeps; unsupported combinations are ignored
+#ifdef SDSTREAM_DEVHOOKS
+  static const char* const tune = getenv("SDSTREAM_TUNE");
+  if (const char* t = tune) {  // "variant,bn,splitk" for sweeps; unsupported combinations are ignored
     int v = -1, bn = 0, sk = 0;
     if (sscanf(t, "%d,%d,%d", &v, &bn, &sk) == 3) {
       if (v >= 0 && v <= 2 && (k64 || v == 0)) c.variant = v;
@@ -713,6 +715,7 @@ Choice choose(const IgemmParams& p) {
         c.splitk = sk;
     }
   }
+#endif
   return c;
 }
 

@@ -1,5 +1,6 @@
 // GroupNorm (+SiLU) over one or two concatenated NHWC sources, and LayerNorm over token rows.
-// Statistics are accumulated in double and applied in fp32, whatever the storage type.
+// The float32 kernels accumulate their statistics in double; the bf16 kernels sum in float32 per thread and per
+// block and fold the block partials in double, in a fixed order.  Normalisation is applied in float32.
 #include "common.h"
 
 namespace {

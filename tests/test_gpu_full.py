@@ -13,7 +13,7 @@ import torch
 
 from workloads import CONFIGS, ssf_frames, stream_inputs
 
-from util import cuda, gpu_engine, rel_l2, rel_max
+from util import TOL_BF16_MAX, check_bf16, cuda, gpu_engine, rel_l2, rel_max
 
 pytestmark = pytest.mark.gpu
 
@@ -24,8 +24,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 
 def _golden(c):
     path = os.path.join(HERE, "golden", f"config{c}.npz")
-    if not os.path.exists(path):
-        pytest.skip(f"{path} missing: run tests/golden/make_golden.py {str(c).replace('_xframe', 'x')}")
+    assert os.path.exists(path), f"{path} missing: run tests/golden/make_golden.py {str(c).replace('_xframe', 'x')}"
     return np.load(path)
 
 
@@ -85,7 +84,7 @@ def _run_stream(c, mode, frames, check_seq=(), cross_frame=0):
         outs[k] = got
         if k < int(gold["frames"]) and valid:
             assert bool(gold[f"mode{mode}_valid{k}"])
-            errs.append(rel_l2(got[:1], gold[f"mode{mode}_frame{k}"]))
+            errs.append(check_bf16(got[:1], gold[f"mode{mode}_frame{k}"], f"config {c} mode {mode} frame {k}")[0])
     assert len(errs) == int(gold["frames"]) - (n - 1)
     seq_errs = []
     for (f, s) in check_seq:          # frame f of stream s leaves the queue at call f + n - 1
@@ -103,7 +102,7 @@ def test_config2_single_step_sd21_shape():
     eps = torch.empty(1, 4, 64, 64, device="cuda")
     eng.unet_forward(cuda(inp["x0"][0][:1]), [999], cuda(inp["context"]), eps)
     torch.cuda.synchronize()
-    assert rel_l2(eps.cpu().numpy(), gold["eps_row0"]) <= TOL_BF16
+    check_bf16(eps.cpu().numpy(), gold["eps_row0"], "config 2 eps")
     eng.close()
     errs, _ = _run_stream(2, 0, 2)
     assert max(errs) <= TOL_BF16
@@ -117,11 +116,75 @@ def test_config3_stream_batch_of_four():
     eps = torch.empty(1, 4, 64, 64, device="cuda")
     eng.unet_forward(cuda(inp["x0"][0][:1]), [999], cuda(inp["context"]), eps)
     torch.cuda.synchronize()
-    assert rel_l2(eps.cpu().numpy(), gold["eps_row0"]) <= TOL_BF16
+    check_bf16(eps.cpu().numpy(), gold["eps_row0"], "config 3 eps")
     eng.close()
     errs, seq = _run_stream(3, 0, 40, check_seq=[(2, 0), (33, 0)])
     assert max(errs) <= TOL_BF16
     assert max(seq) <= TOL_SEQ
+
+
+def _long_run(c, frames, sampled):
+    """The whole stated frame count through the rolling queue; Stream Batch == sequential denoising (Sec. 3.1) on
+    the sampled frames, with the sequential side made of single-row U-Net calls and float64 scheduler arithmetic."""
+    wl = CONFIGS[c]
+    ts = list(wl["timesteps"])
+    n = len(ts)
+    inp = stream_inputs(wl, frames)
+    eng = gpu_engine(wl, "bf16", cfg_mode=0)
+    eng.set_noise(inp["noise"])
+    ctx = cuda(inp["context"])
+    out = torch.empty(1, *inp["x0"].shape[2:], device="cuda")
+    keep = {f + n - 1 for f in sampled}
+    outs, prev = {}, None
+    for k in range(frames):
+        valid = eng.step(cuda(inp["x0"][k]), ctx, None, 1, ts, 1.0, 1.0, out)
+        assert valid == (k >= n - 1)
+        if k in keep or k % 64 == 63:
+            torch.cuda.synchronize()
+            got = out.cpu().numpy().copy()
+            assert np.isfinite(got).all(), k
+            assert prev is None or not np.array_equal(got, prev), k     # the queue moves
+            prev = got
+            if k in keep:
+                outs[k] = got
+    torch.cuda.synchronize()
+    worst = 0.0
+    for f in sampled:
+        want = _sequential_on_gpu(eng, inp["x0"][f, 0], ts, inp["noise"][:, 0], ctx, None, 0, 1.0, 1.0)
+        l2, mx = rel_l2(outs[f + n - 1][0], want), rel_max(outs[f + n - 1][0], want)
+        print(f"config {c} frame {f}: stream vs sequential rel_l2 {l2:.3e}, max|g-o|/max|o| {mx:.3e}")
+        assert l2 <= TOL_SEQ and mx <= TOL_BF16_MAX, (f, l2, mx)
+        worst = max(worst, l2)
+    eng.close()
+    return inp, outs
+
+
+def test_config3_all_512_frames_through_the_queue():
+    sampled = [0, 1, 63, 200, 401, 450, 499, 508]
+    _long_run(3, CONFIGS[3]["frames"], sampled)
+
+
+def test_config2_all_256_frames_and_the_float32_kernels():
+    # n = 1: every call is a whole denoising; sampled frames are also run on the float32 kernels of the library (a
+    # second, independent opinion at full size: different kernels, no bf16 activations)
+    from workloads import make_weights
+    import paper_2312_12491_amd as sd
+    wl = CONFIGS[2]
+    sampled = [0, 31, 77, 128, 201, 230, 254, 255]
+    inp, outs = _long_run(2, wl["frames"], sampled)
+    ts = list(wl["timesteps"])
+    a, b = _schedule(ts)
+    eng = sd.Engine(sd.config_from_dict(wl["unet"], wl["latent"], "fp32", 1, 1, 0))
+    eng.load_weights(make_weights(eng.manifest(), wl["seeds"]["weights"], wl["init"], True))
+    eps = torch.empty(1, 4, 64, 64, device="cuda")
+    ctx = cuda(inp["context"])
+    for f in sampled:
+        x = a[0] * inp["x0"][f, 0].astype(np.float64) + b[0] * inp["noise"][0, 0]
+        eng.unet_forward(cuda(x[None].astype(np.float32)), ts, ctx, eps)
+        torch.cuda.synchronize()
+        want = (x - b[0] * eps[0].cpu().numpy().astype(np.float64)) / a[0]
+        check_bf16(outs[f][0], want, f"config 2 frame {f} vs float32 kernels")
+    eng.close()
 
 
 def test_config3_fp32_path_at_full_size():
@@ -155,8 +218,10 @@ def test_config4_guidance_modes(mode):
 
 
 def test_config5_four_streams_768():
+    # (the stored oracle outputs cover stream 0: one float64 row at 96 x 96 takes the oracle about half a minute;
+    # streams 1 - 3 are checked through the sequential property below, which holds per stream)
     wl = CONFIGS[5]
-    errs, seq = _run_stream(5, wl["cfg_mode"], 6, check_seq=[(1, 1), (2, 3)])
+    errs, seq = _run_stream(5, wl["cfg_mode"], 6, check_seq=[(1, 1), (2, 2), (2, 3)])
     assert max(errs) <= TOL_BF16
     assert max(seq) <= TOL_SEQ
 
@@ -185,7 +250,7 @@ def test_hard_threshold_filter_and_run_statistics_bit_exact():
     # longest stuck run; on this sequence the hard threshold processes fewer frames and stays stuck longer
     from oracle import ssf as F
     import paper_2312_12491_amd as sd
-    from paper_2312_12491_amd.ssf_stats import run_filter, statistics
+    from paper_2312_12491_amd.ssf_stats import read_statistics, run_filter
     wl = CONFIGS[1]
     spec = CONFIGS[5]["ssf"]
     eng = sd.Engine(sd.config_from_dict(wl["unet"], wl["latent"], "fp32", 1, 1, 0))
@@ -197,7 +262,7 @@ def test_hard_threshold_filter_and_run_statistics_bit_exact():
         want = [flt(f, k)[0] for k, f in enumerate(frames)]
         got = run_filter(eng, dev, spec["h"], spec["w"], spec["eta"], spec["draw_seed"], hard)
         assert got == want
-        stats[hard] = statistics(got)
+        stats[hard] = read_statistics(eng)      # the library's counters, against the oracle's count of its own list
         assert stats[hard] == F.run_statistics(want)
     assert stats[True]["duty_cycle"] <= stats[False]["duty_cycle"]
     assert stats[True]["longest_skip_run"] >= stats[False]["longest_skip_run"]

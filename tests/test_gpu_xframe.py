@@ -6,7 +6,7 @@ import torch
 
 from workloads import CONFIGS, MINI_CONFIGS, normal, stream_inputs
 
-from util import cuda, gpu_engine, oracle_net, rel_l2, rel_max
+from util import TOL_BF16_MAX, check_bf16, cuda, gpu_engine, oracle_net, rel_l2, rel_max
 
 pytestmark = pytest.mark.gpu
 
@@ -48,7 +48,7 @@ def test_unet_batches_fp32(name, n, groups, extra):
 @pytest.mark.parametrize("name,n,groups,extra", [("mini15", 4, 1, 0), ("mini40", 2, 2, 1)])
 def test_unet_batches_bf16(name, n, groups, extra):
     got, want = _unet_groups(MINI_CONFIGS[name], "bf16", n, groups, extra)
-    assert rel_l2(got, want) <= TOL_BF16
+    check_bf16(got, want, name + " cross-frame")
 
 
 def _stream_case(wl, dtype, mode, gamma, delta, frames, graph=True):
@@ -88,8 +88,10 @@ def test_stream_modes_fp32(mode):
 @pytest.mark.parametrize("mode", [0, 2])
 def test_stream_modes_bf16(mode):
     wl = MINI_CONFIGS["mini15"]       # 1 stream x 4 steps
-    _, worst = _stream_case(wl, "bf16", mode, 1.2, 1.0, 6)
+    worst_max, worst = _stream_case(wl, "bf16", mode, 1.2, 1.0, 6)
+    print(f"mode {mode}: rel_l2 {worst:.3e}, max|g-o|/max|o| {worst_max:.3e}")
     assert worst <= TOL_BF16
+    assert worst_max <= TOL_BF16_MAX
 
 
 def test_option_changes_the_result_and_single_step_ignores_it():

@@ -15,6 +15,19 @@ def rel_l2(g, o):
     return float(np.linalg.norm(g - o) / np.linalg.norm(o))
 
 
+TOL_BF16 = 2e-2       # ||g-o||_2 / ||o||_2 (the stated bf16 tolerance)
+TOL_BF16_MAX = 3e-2   # max|g-o| / max|o|: a guard against a localised defect that a norm over 16 384 values absorbs
+
+
+def check_bf16(g, o, what=""):
+    """Both bf16 criteria on one output; prints what was observed (shown with pytest -s / -rP) and returns the pair."""
+    l2, mx = rel_l2(g, o), rel_max(g, o)
+    print(f"bf16 parity {what}: rel_l2 {l2:.3e} (<= {TOL_BF16:g}), max|g-o|/max|o| {mx:.3e} (<= {TOL_BF16_MAX:g})")
+    assert l2 <= TOL_BF16, (what, l2)
+    assert mx <= TOL_BF16_MAX, (what, mx)
+    return l2, mx
+
+
 def oracle_net(wl, bf16_weights, cross_frame=False):
     from oracle import unet as U
     shape = U.UNetShape.from_dict(wl["unet"])

@@ -42,6 +42,8 @@ def make_weights(manifest: Iterable, seed: int, init: str, bf16_round: bool) -> 
     kind: 'weight' (conv OIHW or linear [out,in]), 'bias', 'gamma', 'beta'.
     init 'n002' : weights and biases ~ N(0, 0.02²); gamma = 1; beta = 0.
     init 'fanin': weights ~ N(0, 1/fan_in); biases ~ N(0, 0.02²); gamma = 1; beta = 0.
+    init 'fanin_affine': as 'fanin' with gamma ~ 1 + N(0, 0.2²) and beta ~ N(0, 0.1²), so that a norm's scale and
+                  shift are visible in the output (folded or fused norm parameters cannot hide behind 1 and 0).
     bf16_round  : round every value to a bf16-representable float32.
     """
     manifest = list(manifest)
@@ -51,15 +53,15 @@ def make_weights(manifest: Iterable, seed: int, init: str, bf16_round: bool) -> 
     for name, shape, kind in manifest:
         n = int(np.prod(shape))
         if kind == "gamma":
-            blob[off:off + n] = 1.0
+            blob[off:off + n] = 1.0 + normal(seed, name, (n,), 0.2) if init == "fanin_affine" else 1.0
         elif kind == "beta":
-            blob[off:off + n] = 0.0
+            blob[off:off + n] = normal(seed, name, (n,), 0.1) if init == "fanin_affine" else 0.0
         elif kind == "bias":
             blob[off:off + n] = normal(seed, name, (n,), 0.02)
         elif kind == "weight":
             if init == "n002":
                 std = 0.02
-            elif init == "fanin":
+            elif init in ("fanin", "fanin_affine"):
                 std = 1.0 / float(np.sqrt(np.prod(shape[1:])))
             else:
                 raise ValueError(init)
