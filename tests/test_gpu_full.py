@@ -123,7 +123,7 @@ def test_config3_stream_batch_of_four():
     assert max(seq) <= TOL_SEQ
 
 
-def _long_run(c, frames, sampled):
+def _long_run(c, frames, sampled, keep_all=False):
     """The whole stated frame count through the rolling queue; Stream Batch == sequential denoising (Sec. 3.1) on
     the sampled frames, with the sequential side made of single-row U-Net calls and float64 scheduler arithmetic."""
     wl = CONFIGS[c]
@@ -139,13 +139,13 @@ def _long_run(c, frames, sampled):
     for k in range(frames):
         valid = eng.step(cuda(inp["x0"][k]), ctx, None, 1, ts, 1.0, 1.0, out)
         assert valid == (k >= n - 1)
-        if k in keep or k % 64 == 63:
+        if keep_all or k in keep or k % 64 == 63:
             torch.cuda.synchronize()
             got = out.cpu().numpy().copy()
             assert np.isfinite(got).all(), k
             assert prev is None or not np.array_equal(got, prev), k     # the queue moves
             prev = got
-            if k in keep:
+            if keep_all or k in keep:
                 outs[k] = got
     torch.cuda.synchronize()
     worst = 0.0
@@ -165,25 +165,29 @@ def test_config3_all_512_frames_through_the_queue():
 
 
 def test_config2_all_256_frames_and_the_float32_kernels():
-    # n = 1: every call is a whole denoising; sampled frames are also run on the float32 kernels of the library (a
+    # n = 1: every call is a whole denoising; all 256 frames are also run on the float32 kernels of the library (a
     # second, independent opinion at full size: different kernels, no bf16 activations)
     from workloads import make_weights
     import paper_2312_12491_amd as sd
     wl = CONFIGS[2]
     sampled = [0, 31, 77, 128, 201, 230, 254, 255]
-    inp, outs = _long_run(2, wl["frames"], sampled)
+    inp, outs = _long_run(2, wl["frames"], sampled, keep_all=True)
     ts = list(wl["timesteps"])
     a, b = _schedule(ts)
     eng = sd.Engine(sd.config_from_dict(wl["unet"], wl["latent"], "fp32", 1, 1, 0))
     eng.load_weights(make_weights(eng.manifest(), wl["seeds"]["weights"], wl["init"], True))
     eps = torch.empty(1, 4, 64, 64, device="cuda")
     ctx = cuda(inp["context"])
-    for f in sampled:
+    worst = (0.0, 0.0)
+    for f in range(wl["frames"]):
         x = a[0] * inp["x0"][f, 0].astype(np.float64) + b[0] * inp["noise"][0, 0]
         eng.unet_forward(cuda(x[None].astype(np.float32)), ts, ctx, eps)
         torch.cuda.synchronize()
         want = (x - b[0] * eps[0].cpu().numpy().astype(np.float64)) / a[0]
-        check_bf16(outs[f][0], want, f"config 2 frame {f} vs float32 kernels")
+        l2, mx = rel_l2(outs[f][0], want), rel_max(outs[f][0], want)
+        assert l2 <= TOL_BF16 and mx <= TOL_BF16_MAX, (f, l2, mx)
+        worst = (max(worst[0], l2), max(worst[1], mx))
+    print(f"config 2, 256 frames vs float32 kernels: worst rel_l2 {worst[0]:.3e}, worst max|g-o|/max|o| {worst[1]:.3e}")
     eng.close()
 
 
