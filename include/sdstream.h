@@ -150,6 +150,25 @@ int sdstream_ssf_hard(sdstream_t* h, const uint8_t* frame, int32_t height, int32
  * stuck).  Host pointers, each may be NULL. */
 int sdstream_ssf_run_stats(const sdstream_t* h, int64_t* frames, int64_t* processed, int64_t* longest_skip_run);
 
+/* For callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The measurement and decision of sdstream_ssf with no handle, no allocation (no hipMalloc / hipFree /
+ * allocating routine, on any call) and no host synchronisation: the caller keeps the reference frame, everything is
+ * enqueued on `hip_stream`, results land in device memory.
+ *   frame      device, uint8 [height*width*3], 16-byte aligned
+ *   reference  device, same size and alignment, or NULL (no reference yet: never skipped, P = 0)
+ *   sums_out   device [3] or NULL: dot = I_t.I_ref, |I_t|^2, |I_ref|^2 as exact integers
+ *   skip_out   device int32: 1 to skip, 0 to process (then the caller makes `frame` its reference)
+ *   prob_out   device double or NULL: P of Eq. 9
+ * Same arithmetic and the same draw u(seed, frame_index) as sdstream_ssf_decide.
+ * The per-block partial sums sit in a file-scope device array of 24 KiB that each GPU the library runs on holds
+ * until the process ends; every call on a GPU shares it, so calls that overlap on one GPU (two streams, two
+ * threads) race - serialise them.  Frames larger than SDSTREAM_SSF_STATIC_MAX_BYTES are rejected with
+ * SDSTREAM_E_SHAPE; the message is read with sdstream_last_error(NULL). */
+#define SDSTREAM_SSF_STATIC_MAX_BYTES (1LL << 28)
+int sdstream_ssf_static(const uint8_t* frame, const uint8_t* reference, int32_t height, int32_t width, double eta,
+                        uint64_t seed, uint64_t frame_index, uint64_t* sums_out, int32_t* skip_out, double* prob_out,
+                        void* hip_stream);
+
 /* Waits for the device, then zeroes the queue and the reference latents and clears the filter's reference frame,
  * the filter's run statistics and the warm-up counter. */
 int sdstream_reset(sdstream_t* h);

@@ -6,5 +6,5 @@ fallback: importing works without a GPU (so the symbols can be checked), creatin
 """
 from .binding import (  # noqa: F401
     CFG_FULL, CFG_NONE, CFG_ONETIME, CFG_SELF, Engine, SdstreamError, config_from_dict, lib, ssf_decide,
-    ssf_decide_hard,
+    ssf_decide_hard, ssf_static,
 )

@@ -59,6 +59,8 @@ _SIGNATURES = {
                                     C.POINTER(C.c_double), C.c_void_p]),
     "sdstream_ssf_run_stats": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64),
                                          C.POINTER(C.c_int64)]),
+    "sdstream_ssf_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_uint64, C.c_uint64,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "sdstream_reset": (C.c_int, [C.c_void_p]),
     "sdstream_flops_per_row": (C.c_double, [C.c_void_p]),
     "sdstream_mfma_ceiling": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.c_void_p]),
@@ -118,6 +120,16 @@ def ssf_decide_hard(dot: int, n_t: int, n_ref: int, eta: float):
     sc = C.c_double()
     skip = lib().sdstream_ssf_decide_hard(dot, n_t, n_ref, eta, C.byref(sc))
     return bool(skip), sc.value
+
+
+def ssf_static(frame, reference, height: int, width: int, eta: float, seed: int, frame_index: int, sums_out,
+               skip_out, prob_out, stream: int = 0):
+    """sdstream_ssf_static: torch CUDA tensors (uint8 frames; int64 [3], int32 [1], float64 [1] outputs; reference,
+    sums_out and prob_out may be None).  Enqueues only; raises on a rejected call."""
+    rc = lib().sdstream_ssf_static(_ptr(frame), _ptr(reference), height, width, eta, seed, frame_index,
+                                   _ptr(sums_out), _ptr(skip_out), _ptr(prob_out), stream or None)
+    if rc < 0:
+        raise SdstreamError(rc, lib().sdstream_last_error(None).decode())
 
 
 def _ptr(t) -> Optional[int]:
