@@ -60,7 +60,23 @@ struct IgemmParams {
   int xcd_chunked;       // set by the MFMA launcher: block -> tile order (see tile_of_block)
   const void* zeros;     // MFMA kernel only: >= 16 readable zero bytes (source of padded / out-of-range rows)
   FastDiv fd_hw, fd_w, fd_ct, fd_ks, fd_n;   // set by the MFMA launcher: Hout*Wout, Wout, C1+C2, ksize, N
+  // MFMA kernels only.  A LayerNorm in front of a linear layer is folded into it: with W' = W diag(gamma),
+  //   LN(x) W^T = rstd (x W'^T - mean wsum) + beta W^T,   wsum[n] = sum_k W'[n][k],
+  // so the layer multiplies the un-normalised rows, and its epilogue applies mean / rstd of the row, which come from
+  // partial sums that the layer PRODUCING the rows left behind (stats_out of that layer = ln_stats of this one).
+  const float* ln_stats;   // [M][ln_parts][2]: partial (sum, sum of squares) of input row m over a range of its channels; null = no fold
+  int ln_parts;
+  const float* ln_wsum;    // [N]; `W` holds W' and `bias` holds bias + beta W^T
+  float ln_eps;
+  float* stats_out;        // [M][ceil(N/BN)][2] partial sums of this layer's bf16-rounded output rows, one part per column tile; null = none
+  int no_splitk;           // layers with ln_stats or stats_out never split K (their epilogue must see whole sums)
 };
+
+#define LN_MAX_PARTS 20   // most parts of row statistics a folded LayerNorm reads (column tiles of the producing layer)
+
+// Tile geometry the MFMA launcher will pick for p (M set): BN is what stats_out is indexed by.
+struct IgemmPlan { int variant, bm, bn, splitk; };
+IgemmPlan igemm_mfma_plan(const IgemmParams& p);
 
 #define GN_MAX_SPLIT 64
 struct GroupNormParams {
@@ -152,7 +168,14 @@ void launch_ssf_reduce(const uint8_t* frame, const uint8_t* ref, uint8_t* spare,
 //  conv OIHW [O][I][kh][kw] -> T [O][kh*kw][I] (tap-major K), optionally GEGLU row interleave
 template <typename T>
 void launch_repack_rowmajor(const float* src, void* dst, int O, int I, int taps, int geglu_block, hipStream_t s);
-void launch_repack_mfma(const float* src, void* dst, int O, int I, int taps, int geglu_block, hipStream_t s);
+//  `in_scale` (may be null): per input channel factor applied before rounding (the scale of a folded LayerNorm)
+void launch_repack_mfma(const float* src, void* dst, int O, int I, int taps, int geglu_block, const float* in_scale,
+                        hipStream_t s);
+// Vectors of a LayerNorm (gamma, beta over the I input channels) folded into the [O][I] matrix `src`, in the row order
+// of the packed matrix: wsum[n] = sum_i bf16(gamma_i w[n][i]) (what the matrix core multiplies), lnb[n] = sum_i beta_i w[n][i]
+void launch_ln_fold_vectors(const float* src, const float* gamma, const float* beta, float* wsum, float* lnb, int O, int I,
+                            int geglu_block, hipStream_t s);
+void launch_add_f32(float* dst, const float* src, int n, hipStream_t s);
 void launch_permute_bias(const float* src, float* dst, int O, int geglu_block, hipStream_t s);
 template <typename T> void launch_convert(const float* src, void* dst, long long n, hipStream_t s);
 void launch_fill_u32(void* dst, unsigned v, long long n_words, hipStream_t s);

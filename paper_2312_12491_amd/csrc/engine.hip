@@ -96,6 +96,7 @@ struct Op {
   double flops_per_row;  // algorithmic multiply-add work per sample
   double bytes_per_row;  // algorithmic bytes per sample (activations in + out)
   double bytes_fixed;    // weights
+  int ln_src_op;         // >= 0: index of the op whose stats_out this op's folded LayerNorm reads
   // conv_in / conv_out
   const float* cw_f32;
   const void* cw;
@@ -114,7 +115,12 @@ struct Entry {
   int action;
   size_t dst_off;  // bytes into the weight arena
   int O, I, taps, geglu;
+  // a LayerNorm folded into this matrix (LA_MFMA only): byte offsets of the norm's scale / shift and of the two
+  // derived vectors (row sums of the scaled weights, shift times weights) for this entry's rows
+  bool ln_fold = false;
+  size_t ln_g = 0, ln_b = 0, ln_wsum = 0, ln_lnb = 0;
 };
+struct BiasFix { size_t lnb, bias; int n; };   // after loading: lnb[0..n) += bias[0..n)
 
 struct LinW {
   size_t w = 0, b = 0;  // byte offsets into the weight arena (b: fp32)
@@ -140,6 +146,7 @@ struct sdstream {
   bool use_mfma = false;
 
   std::vector<Entry> manifest;
+  std::vector<BiasFix> bias_fixes;
   int64_t n_params = 0;
   size_t weight_bytes = 0;
   char* weights = nullptr;
@@ -252,10 +259,34 @@ struct Builder {
     en.O = O; en.I = I; en.taps = taps; en.geglu = geglu;
     if (dry) e.manifest.push_back(en);
   }
-  float* fvec(const std::string& name, int n, int kind) {
+  size_t fvec_off(const std::string& name, int n, int kind) {
     size_t off = walloc((size_t)n * 4);
     add_entry(name, {n}, kind, LA_F32, off, n, 1, 1, 0);
-    return (float*)(e.weights + off);
+    return off;
+  }
+  float* fvec(const std::string& name, int n, int kind) { return (float*)(e.weights + fvec_off(name, n, kind)); }
+  // LayerNorm (scale at g_off, shift at b_off) folded into `count` stacked matrices of rows_each rows whose weight
+  // entries are the manifest's entries [size - back, size - back + count)
+  struct LnVec { size_t wsum, lnb; };
+  LnVec fold_ln(int count, int rows_each, int back, size_t g_off, size_t b_off) {
+    LnVec v;
+    v.wsum = walloc((size_t)count * rows_each * 4);
+    v.lnb = walloc((size_t)count * rows_each * 4);
+    if (dry) {
+      for (int j = 0; j < count; ++j) {
+        Entry& en = e.manifest[e.manifest.size() - back + j];
+        en.ln_fold = true;
+        en.ln_g = g_off;
+        en.ln_b = b_off;
+        en.ln_wsum = v.wsum + (size_t)j * rows_each * 4;
+        en.ln_lnb = v.lnb + (size_t)j * rows_each * 4;
+      }
+    }
+    return v;
+  }
+  void* aalloc_bytes(size_t bytes_per_sample) {
+    size_t off = e.act.alloc(bytes_per_sample);
+    return e.act_base + off * (size_t)e.max_batch;
   }
   bool mfma_ok(int C1, int C2, int N, bool geglu) const {
     if (!e.use_mfma || !igemm_mfma_available()) return false;
@@ -332,6 +363,7 @@ struct Builder {
     g.residual = residual;
     g.epilogue = epi;
     g.splitk = 1;
+    op.ln_src_op = -1;
     int Nout = epi == EPI_GEGLU ? w.N / 2 : w.N;
     g.out = aalloc((size_t)Hout * Wout * Nout);
     op.rows_per_sample = Hout * Wout;
@@ -466,27 +498,94 @@ struct Builder {
     float* gng = fvec(p + ".norm.g", C, 2);
     float* gnb = fvec(p + ".norm.b", C, 3);
     LinW pin = matw(p + ".proj_in", C, C, 1, false, true, false, C, 0);
-    float* l1g = fvec(p + ".ln1.g", C, 2);
-    float* l1b = fvec(p + ".ln1.b", C, 3);
+    bool fold = mfma_ok(C, 0, C, false) && mfma_ok(C, 0, 8 * C, true) && (C + 159) / 160 <= LN_MAX_PARTS;
+#ifdef SDSTREAM_DEVHOOKS
+    if (getenv("SDSTREAM_NO_LNFOLD")) fold = false;
+#endif
+    const size_t l1g_off = fvec_off(p + ".ln1.g", C, 2), l1b_off = fvec_off(p + ".ln1.b", C, 3);
+    float* l1g = (float*)(e.weights + l1g_off);
+    float* l1b = (float*)(e.weights + l1b_off);
     LinW qkv = fused({p + ".attn1.q", p + ".attn1.k", p + ".attn1.v"}, C, C);
+    LnVec v1{}, v2{}, v3{};
+    if (fold) v1 = fold_ln(3, C, 3, l1g_off, l1b_off);
     LinW o1 = matw(p + ".attn1.o", C, C, 1, false, true, false, C, 0);
-    float* l2g = fvec(p + ".ln2.g", C, 2);
-    float* l2b = fvec(p + ".ln2.b", C, 3);
+    const size_t l2g_off = fvec_off(p + ".ln2.g", C, 2), l2b_off = fvec_off(p + ".ln2.b", C, 3);
+    float* l2g = (float*)(e.weights + l2g_off);
+    float* l2b = (float*)(e.weights + l2b_off);
     LinW q2 = fused({p + ".attn2.q"}, C, C);
+    if (fold) v2 = fold_ln(1, C, 1, l2g_off, l2b_off);
     KVSite site;
     site.w = fused({p + ".attn2.k", p + ".attn2.v"}, C, D);
     site.C = C;
     site.cache = palloc((size_t)2 * L * 2 * C * e.elt);
     e.kv_sites.push_back(site);
     LinW o2 = matw(p + ".attn2.o", C, C, 1, false, true, false, C, 0);
-    float* l3g = fvec(p + ".ln3.g", C, 2);
-    float* l3b = fvec(p + ".ln3.b", C, 3);
+    const size_t l3g_off = fvec_off(p + ".ln3.g", C, 2), l3b_off = fvec_off(p + ".ln3.b", C, 3);
+    float* l3g = (float*)(e.weights + l3g_off);
+    float* l3b = (float*)(e.weights + l3b_off);
     LinW ffi = matw(p + ".ff.in", 8 * C, C, 1, false, true, true, C, 0);
+    if (fold) {
+      v3 = fold_ln(1, 8 * C, 2, l3g_off, l3b_off);   // (entries: ff.in.w, ff.in.b)
+      if (dry) e.bias_fixes.push_back(BiasFix{v3.lnb, ffi.b, 8 * C});
+    }
     LinW ffo = matw(p + ".ff.out", C, 4 * C, 1, false, true, false, 4 * C, 0);
     LinW pout = matw(p + ".proj_out", C, C, 1, false, true, false, C, 0);
 
     void* t = gn(x, C, nullptr, 0, HW, 1e-6f, 0, gng, gnb, stats_buf());
     void* h = conv(t, C, nullptr, 0, H, W, H, W, 1, 1, 0, pin, nullptr, 0, nullptr, EPI_NONE);
+    // With the matrix-core kernels the three LayerNorms are folded into the layers that consume them: the producer of
+    // the rows (proj_in, the two attention output projections) leaves per-row partial sums, the consumer (q/k/v, the
+    // cross-attention q, the feed-forward input) multiplies the raw rows by weights pre-scaled with the norm's scale.
+    const size_t stat_bytes = (size_t)HW * ((C + 63) / 64) * 2 * sizeof(float);
+    // (the statistics buffer is taken while the inputs of the op are still allocated: it must not alias them)
+    auto emit_stats = [&]() {   // the op just emitted also writes row statistics; returns (buffer, op index)
+      void* sb = aalloc_bytes(stat_bytes);
+      e.ops.back().g.stats_out = (float*)sb;
+      e.ops.back().g.no_splitk = 1;
+      return std::make_pair(sb, (int)e.ops.size() - 1);
+    };
+    auto read_stats = [&](std::pair<void*, int> st, const LnVec& v) {   // the op just emitted has the LayerNorm folded in
+      IgemmParams& g = e.ops.back().g;
+      g.ln_stats = (const float*)st.first;
+      g.ln_wsum = (const float*)(e.weights + v.wsum);
+      g.bias = (const float*)(e.weights + v.lnb);
+      g.ln_eps = 1e-5f;
+      g.no_splitk = 1;
+      e.ops.back().ln_src_op = st.second;
+    };
+    if (fold) {
+      auto st1 = emit_stats();
+      afree(t);
+      void* qk = conv(h, C, nullptr, 0, H, W, H, W, 1, 1, 0, qkv, nullptr, 0, nullptr, EPI_NONE);
+      read_stats(st1, v1);
+      afree(st1.first);
+      char* qkb = (char*)qk;
+      void* a1 = attn(qkb, 3 * C, qkb + (size_t)C * e.elt, qkb + (size_t)2 * C * e.elt, 3 * C, HW, HW, heads, d, false, 0);
+      afree(qk);
+      void* h2 = conv(a1, C, nullptr, 0, H, W, H, W, 1, 1, 0, o1, nullptr, 0, h, EPI_NONE);
+      auto st2 = emit_stats();
+      afree(a1);
+      afree(h);
+      void* qc = conv(h2, C, nullptr, 0, H, W, H, W, 1, 1, 0, q2, nullptr, 0, nullptr, EPI_NONE);
+      read_stats(st2, v2);
+      afree(st2.first);
+      char* cache = e.persist + site.cache;
+      void* a2 = attn(qc, C, cache, cache + (size_t)C * e.elt, 2 * C, HW, L, heads, d, true, (size_t)L * 2 * C);
+      afree(qc);
+      void* h3 = conv(a2, C, nullptr, 0, H, W, H, W, 1, 1, 0, o2, nullptr, 0, h2, EPI_NONE);
+      auto st3 = emit_stats();
+      afree(a2);
+      afree(h2);
+      void* u = conv(h3, C, nullptr, 0, H, W, H, W, 1, 1, 0, ffi, nullptr, 0, nullptr, EPI_GEGLU);
+      read_stats(st3, v3);
+      afree(st3.first);
+      void* h4 = conv(u, 4 * C, nullptr, 0, H, W, H, W, 1, 1, 0, ffo, nullptr, 0, h3, EPI_NONE);
+      afree(u);
+      afree(h3);
+      void* out = conv(h4, C, nullptr, 0, H, W, H, W, 1, 1, 0, pout, nullptr, 0, x, EPI_NONE);
+      afree(h4);
+      return out;
+    }
     afree(t);
     // self-attention
     void* n1 = ln(h, HW, C, l1g, l1b);
@@ -755,6 +854,16 @@ void ssf_count(sdstream* h, bool skipped) {
 // ------------------------------------------------------------------------------------------------
 // launching
 // ------------------------------------------------------------------------------------------------
+// the parameter block of a matrix-core GEMM op as it is launched on N rows (also what its tile plan is asked with)
+IgemmParams mfma_params(sdstream* h, const Op& op0, int N) {
+  IgemmParams g = op0.g;
+  g.M = N * op0.rows_per_sample;
+  g.zeros = h->persist + h->off_zeros;
+  g.workspace = (float*)(h->persist + h->off_splitk);
+  g.workspace_floats = (long long)kSplitKWorkspaceFloats;
+  return g;
+}
+
 void launch_op(sdstream* h, const Op& op0, int N, const int* kv_select, int xframe_rows, hipStream_t s) {
   const bool bf = h->cfg.dtype == 1;
   switch (op0.kind) {
@@ -763,8 +872,12 @@ void launch_op(sdstream* h, const Op& op0, int N, const int* kv_select, int xfra
       g.M = N * op0.rows_per_sample;
       g.zeros = h->persist + h->off_zeros;
       if (op0.mfma) {
-        g.workspace = (float*)(h->persist + h->off_splitk);
-        g.workspace_floats = (long long)kSplitKWorkspaceFloats;
+        g = mfma_params(h, op0, N);
+        if (op0.ln_src_op >= 0) {   // one part of row statistics per column tile of the producing layer
+          const IgemmParams pg = mfma_params(h, h->ops[op0.ln_src_op], N);
+          const int bn = igemm_mfma_plan(pg).bn;
+          g.ln_parts = (pg.N + bn - 1) / bn;
+        }
         launch_igemm_mfma(g, s);
       }
       else if (bf) launch_igemm_generic<bf16_t>(g, s);
@@ -1048,7 +1161,16 @@ int sdstream_load_weights(sdstream_t* h, const void* host_blob, size_t bytes) {
         if (bf) launch_repack_rowmajor<bf16_t>(stage, dst, en.O, en.I, en.taps, en.geglu, s);
         else launch_repack_rowmajor<float>(stage, dst, en.O, en.I, en.taps, en.geglu, s);
         break;
-      case LA_MFMA: launch_repack_mfma(stage, dst, en.O, en.I, en.taps, en.geglu, s); break;
+      case LA_MFMA:
+        if (en.ln_fold) {
+          launch_repack_mfma(stage, dst, en.O, en.I, en.taps, en.geglu, (const float*)(h->weights + en.ln_g), s);
+          launch_ln_fold_vectors(stage, (const float*)(h->weights + en.ln_g), (const float*)(h->weights + en.ln_b),
+                                 (float*)(h->weights + en.ln_wsum), (float*)(h->weights + en.ln_lnb), en.O, en.I,
+                                 en.geglu, s);
+        } else {
+          launch_repack_mfma(stage, dst, en.O, en.I, en.taps, en.geglu, nullptr, s);
+        }
+        break;
       case LA_BIAS_PERM: launch_permute_bias(stage, (float*)dst, en.O, en.geglu, s); break;
     }
     er = hipDeviceSynchronize();
@@ -1056,6 +1178,9 @@ int sdstream_load_weights(sdstream_t* h, const void* host_blob, size_t bytes) {
   }
   hipFree(stage);
   if (rc) return rc;
+  for (const BiasFix& f : h->bias_fixes)   // bias + shift-times-weights of a folded LayerNorm, once both are there
+    launch_add_f32((float*)(h->weights + f.lnb), (const float*)(h->weights + f.bias), f.n, s);
+  HIP_TRY(h, hipDeviceSynchronize());
   h->weights_loaded = true;
   h->temb_cached.clear();
   h->kv_valid = false;

@@ -43,6 +43,45 @@ __device__ __forceinline__ float gelu_erf(float x) {
 
 template <int I> struct IC { static constexpr int value = I; };
 
+// sum over the four lanes {l, l^16, l^32, l^48} (the lanes that hold one output row), on the vector ALU:
+// v_permlane16_swap / v_permlane32_swap with both operands equal leave (x[l], x[l^16]) resp. (x[l], x[l^32]) in a lane
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float quad_sum(float x) {
+  u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// mean and 1/std of the block's input rows for a folded LayerNorm, from the partial sums the producing layer left:
+// thread r < BM folds the parts of row m0 + r and leaves (mean, rstd) in LDS for the epilogue.  (Requesting the
+// parts before the main loop and folding them after it, which takes the wait out of the prologue, was measured: it
+// needs the parts in registers across the loop, and with the part count capped to keep that affordable the
+// producing layers lose their best tile width - 7.03 ms per step against 6.94.)
+__device__ __forceinline__ void ln_rows_to_lds(const IgemmParams& p, int m0, int BM, float* lnrow) {
+  const int r = threadIdx.x;
+  if (p.ln_stats == nullptr || r >= BM) return;
+  const int m = min(m0 + r, p.M - 1);
+  const float2* src = (const float2*)p.ln_stats + (long long)m * p.ln_parts;
+  // all parts requested at once (one memory round trip instead of one per part); surplus slots re-read the last part
+  float2 v[LN_MAX_PARTS];
+#pragma unroll
+  for (int i = 0; i < LN_MAX_PARTS; ++i) v[i] = src[min(i, p.ln_parts - 1)];
+  float s = 0.f, q = 0.f;
+#pragma unroll
+  for (int i = 0; i < LN_MAX_PARTS; ++i) {
+    if (i < p.ln_parts) {
+      s += v[i].x;
+      q += v[i].y;
+    }
+  }
+  const float inv = 1.0f / (float)p.K;
+  const float mean = s * inv;
+  const float var = fmaxf(q * inv - mean * mean, 0.f);
+  lnrow[r * 2] = mean;
+  lnrow[r * 2 + 1] = 1.0f / sqrtf(var + p.ln_eps);
+}
+
 // Block -> tile mapping.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  In the natural
 // order (m-tile fastest) an XCD therefore sees every 8th m-tile of every weight column: the activations are split
 // over the L2s and the weights are fetched by all eight - right when the activations are the larger operand.  When
@@ -71,6 +110,7 @@ __device__ __forceinline__ TileId tile_of_block(const FastDiv& mtiles, const Fas
 template <int MT, int NT> struct EpilogueIn {
   f32x4 biasv[NT];       // bias; loaded values are not touched before epilogue_store (a use would wait for them)
   f32x4 rbv[NT];         // time-embedding bias when all rows of the wave belong to one sample
+  f32x4 wsv[NT];         // folded LayerNorm: row sums of the scaled weights
   bf16x4 rv[MT][NT];     // residual
   bool one_sample;
 };
@@ -94,6 +134,7 @@ __device__ __forceinline__ void epilogue_load(const IgemmParams& p, EpilogueIn<M
     const float* rsrc = in.one_sample ? p.rowbias + (long long)sample0 * p.rowbias_ld + n : (const float*)p.zeros;
     in.biasv[nt] = *(const f32x4*)bsrc;
     in.rbv[nt] = *(const f32x4*)rsrc;
+    in.wsv[nt] = *(const f32x4*)(p.ln_wsum ? p.ln_wsum + n : (const float*)p.zeros);
   }
   if (res && p.epilogue != EPI_GEGLU) {
 #pragma unroll
@@ -108,11 +149,22 @@ __device__ __forceinline__ void epilogue_load(const IgemmParams& p, EpilogueIn<M
   }
 }
 
+// lnrow / red: LDS, [rows of the block][2], already offset to this wave's first row; wn: the wave's column half;
+// ntile, ntiles: the block's column tile and their number (index of the row statistics it writes)
 template <int MT, int NT>
 __device__ __forceinline__ void epilogue_store(const IgemmParams& p, f32x4 (&acc)[MT][NT],
                                                const EpilogueIn<MT, NT>& in, int mbase, int gnt0, int lane, int HWo,
-                                               int split) {
+                                               int split, const float* lnrow, float* red, int wn, int ntile,
+                                               int ntiles) {
   const int Nout = p.epilogue == EPI_GEGLU ? p.N >> 1 : p.N;
+  if (p.ln_stats) {   // folded LayerNorm: rstd (x W'^T - mean wsum)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const float mean = lnrow[(mt * 16 + (lane & 15)) * 2], rstd = lnrow[(mt * 16 + (lane & 15)) * 2 + 1];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (acc[mt][nt] - mean * in.wsv[nt]) * rstd;
+    }
+  }
   bf16_t* out = (bf16_t*)p.out;
   const bool has_res = p.residual != nullptr;
   const int ncol = (lane >> 4) * 4;
@@ -152,8 +204,11 @@ __device__ __forceinline__ void epilogue_store(const IgemmParams& p, f32x4 (&acc
     }
     return;
   }
+  float ssum[MT], ssq[MT];   // per output row: sum and sum of squares of what is stored (for a LayerNorm folded into the next layer)
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
+    ssum[mt] = 0.f;
+    ssq[mt] = 0.f;
     const int m = mbase + mt * 16 + (lane & 15);
     if (m >= p.M) continue;
     const int sample = fast_div(m, p.fd_hw);
@@ -171,18 +226,44 @@ __device__ __forceinline__ void epilogue_store(const IgemmParams& p, f32x4 (&acc
 #pragma unroll
       for (int v = 0; v < 4; ++v) o[v] = (bf16_t)x[v];
       *(bf16x4*)(out + (long long)m * Nout + n) = o;
+      if (p.stats_out) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const float r = (float)o[v];
+          ssum[mt] += r;
+          ssq[mt] = fmaf(r, r, ssq[mt]);
+        }
+      }
+    }
+  }
+  if (p.stats_out) {   // block-uniform: the two waves that share rows add up through LDS, one part per column tile
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      ssum[mt] = quad_sum(ssum[mt]);
+      ssq[mt] = quad_sum(ssq[mt]);
+    }
+    __syncthreads();   // every wave is done with the tiles in LDS
+    if (wn == 1 && lane < 16) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        red[(mt * 16 + lane) * 2] = ssum[mt];
+        red[(mt * 16 + lane) * 2 + 1] = ssq[mt];
+      }
+    }
+    __syncthreads();
+    if (wn == 0 && lane < 16) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const int m = mbase + mt * 16 + lane;
+        if (m >= p.M) continue;
+        float2 o;
+        o.x = ssum[mt] + red[(mt * 16 + lane) * 2];
+        o.y = ssq[mt] + red[(mt * 16 + lane) * 2 + 1];
+        *((float2*)p.stats_out + (long long)m * ntiles + ntile) = o;
+      }
     }
   }
 }
-
-template <int MT, int NT>
-__device__ __forceinline__ void epilogue(const IgemmParams& p, f32x4 (&acc)[MT][NT], int mbase, int gnt0, int lane,
-                                         int HWo, int split) {
-  EpilogueIn<MT, NT> in;
-  epilogue_load<MT, NT>(p, in, mbase, gnt0, lane, HWo);
-  epilogue_store<MT, NT>(p, acc, in, mbase, gnt0, lane, HWo, split);
-}
-
 
 template <int BM, int BN, int NSETS>
 __global__ __launch_bounds__(256, 2) void igemm_mfma_kernel(IgemmParams p, FastDiv mtiles, FastDiv ntiles, int ksteps_total,
@@ -194,6 +275,7 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma_kernel(IgemmParams p, FastD
   constexpr int NLD = BM * CPR / 256;  // chunks each thread stages
   constexpr int D = NSETS - 1;         // prefetch distance in 32-deep K stages
   __shared__ __attribute__((aligned(16))) unsigned char lds[2][BM * ROWB];
+  __shared__ float lnrow[BM * 2], red[BM * 2];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave & 1, wn = wave >> 1;
@@ -201,6 +283,7 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma_kernel(IgemmParams p, FastD
   if (!tile.valid) return;  // padding block (uniform for the whole block, before any barrier)
   const int mtile = tile.mtile, ntile = tile.ntile;
   const int m0 = mtile * BM, n0 = ntile * BN;
+  ln_rows_to_lds(p, m0, BM, lnrow);   // read by the epilogue, after the barriers of the main loop
   const int Ct = p.C1 + p.C2;
   const int pad = p.ksize >> 1;
   const int HWo = p.Hout * p.Wout;
@@ -337,7 +420,10 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma_kernel(IgemmParams p, FastD
     }
   }
 
-  epilogue<MT, NT>(p, acc, m0 + wm * WTM, gnt0, lane, HWo, tile.split);
+  EpilogueIn<MT, NT> epi_in;
+  epilogue_load<MT, NT>(p, epi_in, m0 + wm * WTM, gnt0, lane, HWo);
+  epilogue_store<MT, NT>(p, acc, epi_in, m0 + wm * WTM, gnt0, lane, HWo, tile.split, lnrow + wm * WTM * 2,
+                         red + wm * WTM * 2, wn, ntile, (int)ntiles.d);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -412,6 +498,8 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, FastDi
   const char* Wp = (const char*)p.W;
   const char* zeros = (const char*)p.zeros;
   const unsigned lds0 = (unsigned)(unsigned long long)(__attribute__((address_space(3))) void*)lds;
+  float* lnrow = (float*)(lds + NBUF * STAGE);   // [BM][2] mean, rstd of the input rows (folded LayerNorm)
+  float* red = lnrow + BM * 2;                   // [BM][2] row statistics of the other column half
 
   // A loads of this lane: load i of wave w fills LDS rows (i*NW + w)*8 .. +7
   int ld_y[NLA], ld_x[NLA];
@@ -527,6 +615,8 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, FastDi
 #pragma unroll
   for (int b = 0; b < NBUF; ++b)
     if (b < nstages) issue(b);
+  // after the first stages are on their way: the wait for these loads also waits for those, which the loop would do next anyway
+  ln_rows_to_lds(p, m0, BM, lnrow);
 
   // Rotated loop: the MFMAs of a stage's second k-step are issued together with the fragment reads of the next
   // stage's first k-step, so half of the LDS read latency sits in the shadow of the matrix cores.
@@ -571,7 +661,8 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, FastDi
   }
   if (nstages > 0) mfmas(1);
   if constexpr (BM != 64) epilogue_load<MT, NT>(p, epi_in, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo);
-  epilogue_store<MT, NT>(p, acc, epi_in, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo, tile.split);
+  epilogue_store<MT, NT>(p, acc, epi_in, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo, tile.split,
+                         lnrow + wm * WTM * 2, red + wm * WTM * 2, wn, tile.ntile, (int)ntiles.d);
 }
 
 // split-K finalize: sum of the partials (fp32 [splitk][M][N]) -> out with the epilogue of the main kernel
@@ -622,7 +713,7 @@ template <int BM, int BN, int NSETS> void launch_cfg(const IgemmParams& p, hipSt
 }
 
 template <int BM, int BN, int NBUF> void launch_dma(const IgemmParams& p, hipStream_t s) {
-  constexpr int LDS = NBUF * (BM + BN) * 128;
+  constexpr int LDS = NBUF * (BM + BN) * 128 + BM * 16;   // stages, then two [BM][2] float arrays of row statistics
   static bool attr_set = false;
   if (!attr_set) {
     hipFuncSetAttribute((const void*)igemm_dma_kernel<BM, BN, NBUF>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
@@ -657,9 +748,13 @@ Choice choose(const IgemmParams& p) {
   const int bn0 = geglu ? 128 : p.N % 160 == 0 ? 160 : p.N % 128 == 0 ? 128 : 64;
   c.bn = bn0;
   c.splitk = 1;
-  if (!k64) { c.variant = 0; return c; }
+  if (!k64) {
+    c.variant = 0;
+    if (p.stats_out && (p.N + c.bn - 1) / c.bn > LN_MAX_PARTS) c.bn = 160;
+    return c;
+  }
   const int stages = p.K / 64;
-  const bool may_split = p.epilogue == EPI_NONE && p.workspace != nullptr;
+  const bool may_split = p.epilogue == EPI_NONE && p.workspace != nullptr && !p.no_splitk;
   const long long mn = (long long)p.M * p.N;
   auto blocks = [&](int bm, int bn) { return ((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn); };
   // K splits for a grid of nb tiles: up to one block per compute unit, two where a block would walk > 100 stages
@@ -700,6 +795,8 @@ Choice choose(const IgemmParams& p) {
     const int nb = blocks(64, c.bn);
     if (nb < 64 && stages >= 16) sk = split_for(nb);
   }
+  // a layer that leaves row statistics writes one part per column tile, and the reader takes at most LN_MAX_PARTS
+  if (p.stats_out && (p.N + c.bn - 1) / c.bn > LN_MAX_PARTS) c.bn = 160;
   if (!may_split) sk = 1;
   if ((long long)sk * mn > p.workspace_floats) sk = (int)(p.workspace_floats / mn);
   c.splitk = sk > 1 ? sk : 1;
@@ -731,6 +828,21 @@ template <int BN> void launch_bn(const IgemmParams& p, int variant, hipStream_t 
 
 bool igemm_mfma_available() { return true; }
 
+IgemmPlan igemm_mfma_plan(const IgemmParams& p) {
+  const Choice c = choose(p);
+  IgemmPlan r;
+  r.variant = c.variant;
+  r.bm = c.variant == 2 ? 64 : 128;
+  r.bn = c.bn;
+  r.splitk = c.splitk;
+  if (r.splitk > 1) {  // drop splits that the rounding of stages per split leaves empty
+    const int stages = c.variant == 0 ? p.K / 32 : p.K / 64;
+    const int sps = (stages + r.splitk - 1) / r.splitk;
+    r.splitk = (stages + sps - 1) / sps;
+  }
+  return r;
+}
+
 bool igemm_mfma_supported(const IgemmParams& p) {
   if (p.C1 % 32 || p.C2 % 32 || p.N % 16) return false;
   if (p.epilogue == EPI_GEGLU && p.N % 128) return false;
@@ -746,13 +858,8 @@ bool igemm_mfma_supported(const IgemmParams& p) {
 
 void launch_igemm_mfma(const IgemmParams& p0, hipStream_t s) {
   IgemmParams p = p0;
-  const Choice c = choose(p);
+  const IgemmPlan c = igemm_mfma_plan(p);
   p.splitk = c.splitk;
-  if (p.splitk > 1) {  // drop splits that the rounding of stages per split leaves empty
-    const int stages = c.variant == 0 ? p.K / 32 : p.K / 64;
-    const int sps = (stages + p.splitk - 1) / p.splitk;
-    p.splitk = (stages + sps - 1) / sps;
-  }
   p.xcd_chunked = (long long)p.N * p.K > (long long)p.M * (p.C1 + p.C2) ? 1 : 0;
   p.fd_hw = make_fastdiv((unsigned)(p.Hout * p.Wout));
   p.fd_w = make_fastdiv((unsigned)p.Wout);

@@ -309,7 +309,7 @@ __global__ void repack_rowmajor_kernel(const float* src, T* dst, int O, int I, i
 
 // MFMA B-fragment order for v_mfma_f32_16x16x32_bf16: dst[ntile][kstep][lane][8] with
 // column n = ntile*16 + lane%16 and k = kstep*32 + (lane/16)*8 + j, k = tap*I + i.
-__global__ void repack_mfma_kernel(const float* src, bf16_t* dst, int O, int I, int taps, int blk) {
+__global__ void repack_mfma_kernel(const float* src, bf16_t* dst, int O, int I, int taps, int blk, const float* in_scale) {
   long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   long long K = (long long)I * taps;
   long long total = (long long)O * K;
@@ -324,7 +324,29 @@ __global__ void repack_mfma_kernel(const float* src, bf16_t* dst, int O, int I, 
   long long k = (long long)kstep * 32 + (lane >> 4) * 8 + j;
   int tap = (int)(k / I), i = (int)(k - (long long)tap * I);
   int so = geglu_src_row(n, O, blk);
-  dst[idx] = (bf16_t)src[((long long)so * I + i) * taps + tap];
+  float w = src[((long long)so * I + i) * taps + tap];
+  if (in_scale) w *= in_scale[i];
+  dst[idx] = (bf16_t)w;
+}
+
+// one thread per packed row n; double accumulation (these vectors carry the whole mean term of the folded norm)
+__global__ void ln_fold_vectors_kernel(const float* src, const float* gamma, const float* beta, float* wsum, float* lnb,
+                                       int O, int I, int blk) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= O) return;
+  const float* row = src + (long long)geglu_src_row(n, O, blk) * I;
+  double ws = 0.0, lb = 0.0;
+  for (int i = 0; i < I; ++i) {
+    ws += (double)(float)(bf16_t)(row[i] * gamma[i]);
+    lb += (double)row[i] * (double)beta[i];
+  }
+  wsum[n] = (float)ws;
+  lnb[n] = (float)lb;
+}
+
+__global__ void add_f32_kernel(float* dst, const float* src, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] += src[i];
 }
 
 __global__ void permute_bias_kernel(const float* src, float* dst, int O, int blk) {
@@ -415,10 +437,21 @@ void launch_repack_rowmajor(const float* src, void* dst, int O, int I, int taps,
 template void launch_repack_rowmajor<float>(const float*, void*, int, int, int, int, hipStream_t);
 template void launch_repack_rowmajor<bf16_t>(const float*, void*, int, int, int, int, hipStream_t);
 
-void launch_repack_mfma(const float* src, void* dst, int O, int I, int taps, int geglu_block, hipStream_t s) {
+void launch_repack_mfma(const float* src, void* dst, int O, int I, int taps, int geglu_block, const float* in_scale,
+                        hipStream_t s) {
   long long total = (long long)O * I * taps;
   hipLaunchKernelGGL(repack_mfma_kernel, dim3(blocks_for(total, 256, 1LL << 31)), dim3(256), 0, s, src, (bf16_t*)dst, O,
-                     I, taps, geglu_block);
+                     I, taps, geglu_block, in_scale);
+}
+
+void launch_ln_fold_vectors(const float* src, const float* gamma, const float* beta, float* wsum, float* lnb, int O, int I,
+                            int geglu_block, hipStream_t s) {
+  hipLaunchKernelGGL(ln_fold_vectors_kernel, dim3((O + 63) / 64), dim3(64), 0, s, src, gamma, beta, wsum, lnb, O, I,
+                     geglu_block);
+}
+
+void launch_add_f32(float* dst, const float* src, int n, hipStream_t s) {
+  hipLaunchKernelGGL(add_f32_kernel, dim3((n + 255) / 256), dim3(256), 0, s, dst, src, n);
 }
 
 void launch_permute_bias(const float* src, float* dst, int O, int geglu_block, hipStream_t s) {
