@@ -70,6 +70,9 @@ typedef struct {
                                                 /*    V_Batch): every self-attention of a row uses the keys and */
                                                 /*    values of all n rows of its stream (and prompt branch);   */
                                                 /*    0: rows independent                                       */
+  int32_t image_width;                          /* > 0: the engine also owns the latent <-> image stage (a tiny */
+                                                /*    convolutional autoencoder of this width, 64 in the         */
+                                                /*    workloads; needs in_channels = 4); 0: latents only         */
 } sdstream_config;
 
 /* Creates an engine on the current HIP device and allocates all device state.  No weights yet. */
@@ -149,6 +152,33 @@ int sdstream_ssf_hard(sdstream_t* h, const uint8_t* frame, int32_t height, int32
  * paper's power figure follows this share), and the longest run of consecutive skips (how long the output stayed
  * stuck).  Host pointers, each may be NULL. */
 int sdstream_ssf_run_stats(const sdstream_t* h, int64_t* frames, int64_t* processed, int64_t* longest_skip_run);
+
+/* The latent <-> image stage (appendix: the pipeline wraps a tiny autoencoder around the U-Net; the paper names it
+ * and gives no layers, so these are this library's): all convolutions 3x3 with zero padding, one width w,
+ *   Block(x) = ReLU(conv_c(ReLU(conv_b(ReLU(conv_a(x))))) + x)
+ *   encoder : u8 image / 255 -> conv(3 -> w) -> Block -> 3 x [conv stride 2, no bias -> 3 Blocks] -> conv(w -> 4)
+ *   decoder : 3 tanh(latent / 3) -> ReLU(conv(4 -> w)) -> 3 x [3 Blocks -> nearest 2x -> conv, no bias] -> Block
+ *             -> conv(w -> 3) -> clamp to [0,1]; u8 image = round(255 x), ties to even
+ * Images are device u8 [S][8 latent_h][8 latent_w][3] (one per stream), latents device float32 [S][4][h][w].
+ * The stage has its own weight manifest and blob (same conventions as the U-Net's, encoder first).
+ * Only engines created with image_width > 0 have it; the others return SDSTREAM_E_NOT_READY. */
+int64_t sdstream_image_param_count(const sdstream_t* h);
+int32_t sdstream_image_manifest_size(const sdstream_t* h);
+int sdstream_image_manifest_entry(const sdstream_t* h, int32_t index, char* name, size_t name_cap, int32_t shape[4],
+                                  int32_t* ndim, int32_t* kind);
+int sdstream_load_image_weights(sdstream_t* h, const void* host_blob, size_t bytes);
+int sdstream_encode(sdstream_t* h, const uint8_t* image, float* latent_out, void* hip_stream);
+/* image_out (u8) and image_f32_out (float32 [S][3][H][W], the image before quantisation) may each be NULL, not both */
+int sdstream_decode(sdstream_t* h, const float* latent, uint8_t* image_out, float* image_f32_out, void* hip_stream);
+/* sdstream_step with the boundary at the image: encoder -> one Stream Batch step -> decoder, the latents staying in
+ * the engine.  frame: the stream's next input image; image_out: the image of the frame given n-1 calls earlier.
+ * Other arguments, validity and queue behaviour as in sdstream_step.  Replayed as ONE HIP graph per call when the
+ * caller passes the same two image buffers (and gamma, delta) as on the previous call with the same queue parity;
+ * otherwise the graph is captured again first.  (The similarity filter is a host decision taken before this call:
+ * a skipped frame is simply not submitted.) */
+int sdstream_step_image(sdstream_t* h, const uint8_t* frame, const float* context, const float* neg_context,
+                        uint64_t context_epoch, const int32_t* timesteps, float gamma, float delta, uint8_t* image_out,
+                        int32_t* out_valid, void* hip_stream);
 
 /* For callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc.  The measurement and decision of sdstream_ssf with no handle, no allocation (no hipMalloc / hipFree /

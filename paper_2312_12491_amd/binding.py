@@ -24,7 +24,8 @@ class Config(C.Structure):
                 ("head_dim", C.c_int32), ("mid_attention", C.c_int32), ("context_len", C.c_int32),
                 ("context_dim", C.c_int32), ("norm_groups", C.c_int32), ("latent_h", C.c_int32),
                 ("latent_w", C.c_int32), ("dtype", C.c_int32), ("n_denoise", C.c_int32), ("n_streams", C.c_int32),
-                ("cfg_mode", C.c_int32), ("scheduler", C.c_int32), ("cross_frame", C.c_int32)]
+                ("cfg_mode", C.c_int32), ("scheduler", C.c_int32), ("cross_frame", C.c_int32),
+                ("image_width", C.c_int32)]
 
 
 class ProfileEntry(C.Structure):
@@ -43,6 +44,15 @@ _SIGNATURES = {
     "sdstream_manifest_entry": (C.c_int, [C.c_void_p, C.c_int32, C.c_char_p, C.c_size_t, C.POINTER(C.c_int32),
                                           C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "sdstream_load_weights": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t]),
+    "sdstream_image_param_count": (C.c_int64, [C.c_void_p]),
+    "sdstream_image_manifest_size": (C.c_int32, [C.c_void_p]),
+    "sdstream_image_manifest_entry": (C.c_int, [C.c_void_p, C.c_int32, C.c_char_p, C.c_size_t, C.POINTER(C.c_int32),
+                                                C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
+    "sdstream_load_image_weights": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t]),
+    "sdstream_encode": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "sdstream_decode": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "sdstream_step_image": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.POINTER(C.c_int32),
+                                      C.c_float, C.c_float, C.c_void_p, C.POINTER(C.c_int32), C.c_void_p]),
     "sdstream_set_schedule": (C.c_int, [C.c_void_p, C.c_void_p]),
     "sdstream_set_noise": (C.c_int, [C.c_void_p, C.c_void_p]),
     "sdstream_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.POINTER(C.c_int32),
@@ -90,7 +100,7 @@ def exported_symbols():
 
 
 def config_from_dict(unet: dict, latent, dtype: str, n_denoise: int, n_streams: int, cfg_mode: int,
-                     scheduler: int = 0, cross_frame: int = 0) -> Config:
+                     scheduler: int = 0, cross_frame: int = 0, image_width: int = 0) -> Config:
     c = Config()
     ch = list(unet["block_channels"])
     c.in_channels = unet["in_channels"]
@@ -107,6 +117,7 @@ def config_from_dict(unet: dict, latent, dtype: str, n_denoise: int, n_streams: 
     c.dtype = {"fp32": 0, "bf16": 1}[dtype]
     c.n_denoise, c.n_streams, c.cfg_mode, c.scheduler = n_denoise, n_streams, cfg_mode, scheduler
     c.cross_frame = int(cross_frame)
+    c.image_width = int(image_width)
     return c
 
 
@@ -174,16 +185,45 @@ class Engine:
     def flops_per_row(self) -> float:
         return self._l.sdstream_flops_per_row(self._h)
 
-    def manifest(self):
+    def _manifest(self, size_fn, entry_fn):
         out = []
         kinds = {0: "weight", 1: "bias", 2: "gamma", 3: "beta"}
         name = C.create_string_buffer(128)
         shape = (C.c_int32 * 4)()
         ndim, kind = C.c_int32(), C.c_int32()
-        for i in range(self._l.sdstream_manifest_size(self._h)):
-            self._check(self._l.sdstream_manifest_entry(self._h, i, name, 128, shape, C.byref(ndim), C.byref(kind)))
+        for i in range(size_fn(self._h)):
+            self._check(entry_fn(self._h, i, name, 128, shape, C.byref(ndim), C.byref(kind)))
             out.append((name.value.decode(), tuple(shape[j] for j in range(ndim.value)), kinds[kind.value]))
         return out
+
+    def manifest(self):
+        return self._manifest(self._l.sdstream_manifest_size, self._l.sdstream_manifest_entry)
+
+    def image_manifest(self):
+        return self._manifest(self._l.sdstream_image_manifest_size, self._l.sdstream_image_manifest_entry)
+
+    def image_param_count(self) -> int:
+        return self._l.sdstream_image_param_count(self._h)
+
+    def load_image_weights(self, blob):
+        """blob: contiguous float32 numpy array in image-manifest order."""
+        assert blob.dtype.name == "float32" and blob.flags["C_CONTIGUOUS"]
+        self._check(self._l.sdstream_load_image_weights(self._h, blob.ctypes.data, blob.nbytes))
+
+    def encode(self, image, latent_out, stream: int = 0):
+        """image: torch uint8 CUDA [S,H,W,3]; latent_out: float32 CUDA [S,4,H/8,W/8]."""
+        self._check(self._l.sdstream_encode(self._h, _ptr(image), _ptr(latent_out), stream or None))
+
+    def decode(self, latent, image_out=None, image_f32_out=None, stream: int = 0):
+        self._check(self._l.sdstream_decode(self._h, _ptr(latent), _ptr(image_out), _ptr(image_f32_out), stream or None))
+
+    def step_image(self, frame, context, neg_context, context_epoch: int, timesteps: Sequence[int], gamma: float,
+                   delta: float, image_out, stream: int = 0) -> bool:
+        ts = (C.c_int32 * len(timesteps))(*timesteps)
+        valid = C.c_int32()
+        self._check(self._l.sdstream_step_image(self._h, _ptr(frame), _ptr(context), _ptr(neg_context), context_epoch,
+                                                ts, gamma, delta, _ptr(image_out), C.byref(valid), stream or None))
+        return bool(valid.value)
 
     # ---- setup
     def load_weights(self, blob):

@@ -12,7 +12,7 @@ template <typename T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }
 
-enum { EPI_NONE = 0, EPI_GEGLU = 1, EPI_SILU = 2 };
+enum { EPI_NONE = 0, EPI_GEGLU = 1, EPI_SILU = 2, EPI_RELU = 3 };   // RELU is applied after the residual sum
 
 // Division by a launch-time constant through one multiply-high (the round-up method of Granlund and Montgomery):
 // exact for 0 <= x < 2^31.  An integer division by a run-time value costs ~30 instructions on this target, and
@@ -129,13 +129,24 @@ void launch_attention_mfma(const AttnParams& p, hipStream_t s);
 bool attention_mfma_supported(const AttnParams& p);
 
 // conv_in: fp32 NCHW [N,Cin,H,W] -> T NHWC [N,HW,C0]; w fp32 OIHW, 3x3 pad 1.
+// flags: CONV_IN_SQUASH applies 3 tanh(x / 3) to the input (the decoder's latent clamp), CONV_IN_RELU a ReLU to the output.
+enum { CONV_IN_SQUASH = 1, CONV_IN_RELU = 2 };
 template <typename T>
 void launch_conv_in(const float* x, const float* w, const float* b, void* out, int N, int Cin, int H, int W, int C0,
-                    hipStream_t s);
+                    int flags, hipStream_t s);
 // conv_out: T NHWC [N,HW,C0] -> fp32 NCHW [N,Cout,H,W]; w T [Cout][9][C0] (tap-major), 3x3 pad 1.
 template <typename T>
 void launch_conv_out(const void* x, const void* w, const float* b, float* out, int N, int Cout, int H, int W, int C0,
                      hipStream_t s);
+
+// Image side of the tiny autoencoder: u8 HWC image -> first convolution (3 -> C0, x/255, fp32 weights OIHW), and last
+// convolution (C0 -> 3, weights T [3][9][C0]) -> clamp [0,1] -> float NCHW and / or u8 HWC (either may be null).
+template <typename T>
+void launch_image_in(const uint8_t* img, const float* w, const float* b, void* out, int N, int H, int W, int C0,
+                     hipStream_t s);
+template <typename T>
+void launch_image_out(const void* x, const void* w, const float* b, float* out_f32, uint8_t* out_u8, int N, int H, int W,
+                      int C0, hipStream_t s);
 
 // e[row] = [cos(t f_j) ; sin(t f_j)], f_j = exp(-ln(1e4) j/half), evaluated in double.
 void launch_time_embedding(const int* t, float* out, int rows, int C0, hipStream_t s);

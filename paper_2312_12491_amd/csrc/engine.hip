@@ -76,7 +76,7 @@ struct PlanAllocator {
 // split-K is used only for GEMMs with few output tiles; splits * M * N never exceeds this
 constexpr size_t kSplitKWorkspaceFloats = (size_t)16 << 20;
 
-enum OpKind { OP_IGEMM, OP_GN, OP_LN, OP_ATTN, OP_CONV_IN, OP_CONV_OUT };
+enum OpKind { OP_IGEMM, OP_GN, OP_LN, OP_ATTN, OP_CONV_IN, OP_CONV_OUT, OP_IMAGE_IN, OP_IMAGE_OUT };
 enum ProfClass {
   PC_IGEMM_MFMA, PC_IGEMM_VALU, PC_ATTN_MFMA, PC_ATTN_VALU, PC_GROUP_NORM, PC_LAYER_NORM, PC_CONV_IN, PC_CONV_OUT,
   PC_STREAM_HEAD, PC_STREAM_TAIL, PC_COUNT
@@ -97,12 +97,15 @@ struct Op {
   double bytes_per_row;  // algorithmic bytes per sample (activations in + out)
   double bytes_fixed;    // weights
   int ln_src_op;         // >= 0: index of the op whose stats_out this op's folded LayerNorm reads
-  // conv_in / conv_out
+  // conv_in / conv_out (fp32 NCHW <-> NHWC activations) and image_in / image_out (u8 HWC image <-> NHWC activations)
   const float* cw_f32;
   const void* cw;
   const float* cb;
   const void* cin;
   void* cout_;
+  int cH, cW, cCin, cC0, cflags;   // spatial size, channels on the NCHW / image side, channels on the NHWC side
+  float* img_f32;                  // image_out: float NCHW image or null
+  uint8_t* img_u8;                 // image_out: u8 HWC image or null
 };
 
 enum LoadAction { LA_F32, LA_ROWMAJOR, LA_MFMA, LA_BIAS_PERM };
@@ -181,6 +184,20 @@ struct sdstream {
   int cur = 0;
   long long calls = 0;
   double alphas[1000];
+
+  // latent <-> image stage (cfg.image_width > 0): its own manifest, weights, activation arena and op lists
+  std::vector<Entry> img_manifest;
+  int64_t img_n_params = 0;
+  size_t img_weight_bytes = 0;
+  char* img_weights = nullptr;
+  bool img_weights_loaded = false;
+  PlanAllocator img_act;
+  char* img_act_base = nullptr;
+  size_t img_act_bytes = 0;
+  std::vector<Op> img_enc_ops, img_dec_ops;
+  size_t off_img_lat_in = 0, off_img_lat_out = 0;   // fp32 [S][C][h][w] latents between the stage and the step
+  struct ImageGraph { hipGraphExec_t exec = nullptr; const void* frame = nullptr; void* image = nullptr; float gamma = 0, delta = 0; };
+  ImageGraph img_graph[2];   // sdstream_step_image: one captured graph per queue buffer
 
   // ssf
   uint8_t* ssf_buf[2] = {nullptr, nullptr};
@@ -648,6 +665,10 @@ struct Builder {
     e.off_unet_x = palloc((size_t)e.max_batch * e.E * 4);
     e.off_splitk = palloc(kSplitKWorkspaceFloats * 4);
     e.off_zeros = palloc(256);
+    if (c.image_width > 0) {
+      e.off_img_lat_in = palloc((size_t)c.n_streams * e.E * 4);
+      e.off_img_lat_out = palloc((size_t)c.n_streams * e.E * 4);
+    }
 
     // time embedding MLP (float32)
     LinW t1 = f32w("time.lin1", temb_dim, c0);
@@ -682,6 +703,7 @@ struct Builder {
       op.cls = PC_CONV_IN;
       op.cw_f32 = (const float*)(e.weights + ciw);
       op.cb = cib;
+      op.cH = H; op.cW = W; op.cCin = c.in_channels; op.cC0 = c0; op.cflags = 0;
       op.cout_ = aalloc((size_t)H * W * c0);
       op.rows_per_sample = H * W;
       op.flops_per_row = 2.0 * H * W * c0 * c.in_channels * 9;
@@ -769,6 +791,7 @@ struct Builder {
       op.cin = t;
       op.cw = e.weights + cow;
       op.cb = cob;
+      op.cH = H; op.cW = W; op.cCin = c.in_channels; op.cC0 = ch; op.cflags = 0;
       op.rows_per_sample = H * W;
       op.flops_per_row = 2.0 * H * W * c.in_channels * ch * 9;
       op.bytes_per_row = (double)H * W * (c.in_channels * 4 + ch * e.elt);
@@ -777,6 +800,181 @@ struct Builder {
     afree(t);
     e.flops_per_row = 0;
     for (const Op& op : e.ops) e.flops_per_row += op.flops_per_row;
+  }
+};
+
+// ------------------------------------------------------------------------------------------------
+// the latent <-> image stage: a tiny convolutional autoencoder of one width w around the U-Net
+//   Block(x) = ReLU(conv_c(ReLU(conv_b(ReLU(conv_a(x))))) + x)
+//   encoder : u8 image / 255 -> conv(3 -> w) -> Block -> 3 x [conv stride 2 (no bias) -> 3 Blocks] -> conv(w -> C)
+//   decoder : 3 tanh(latent / 3) -> ReLU(conv(C -> w)) -> 3 x [3 Blocks -> nearest 2x -> conv (no bias)] -> Block
+//             -> conv(w -> 3) -> clamp [0,1]
+// (all convolutions 3x3, pad 1).  The paper's appendix only names its autoencoder; these layers are this library's.
+// ------------------------------------------------------------------------------------------------
+struct ImageBuilder {
+  sdstream& e;
+  bool dry;
+  size_t wbytes = 0;
+  std::vector<Op>* ops = nullptr;
+  explicit ImageBuilder(sdstream& eng, bool dry_) : e(eng), dry(dry_) {}
+
+  size_t walloc(size_t bytes) {
+    size_t off = wbytes;
+    wbytes += (bytes + 255) & ~(size_t)255;
+    return off;
+  }
+  void add_entry(const std::string& name, std::initializer_list<int> shape, int kind, int action, size_t dst_off, int O,
+                 int I, int taps) {
+    Entry en;
+    en.name = name;
+    en.ndim = (int)shape.size();
+    en.count = 1;
+    int i = 0;
+    for (int s : shape) { en.shape[i++] = s; en.count *= (size_t)s; }
+    for (; i < 4; ++i) en.shape[i] = 1;
+    en.kind = kind; en.action = action; en.dst_off = dst_off;
+    en.O = O; en.I = I; en.taps = taps; en.geglu = 0;
+    if (dry) e.img_manifest.push_back(en);
+  }
+  float* bias(const std::string& name, int n) {
+    size_t off = walloc((size_t)n * 4);
+    add_entry(name, {n}, 1, LA_F32, off, n, 1, 1);
+    return (float*)(e.img_weights + off);
+  }
+  struct CW { const void* w; const float* b; bool mfma; };
+  CW convw(const std::string& name, int O, int I, bool with_bias) {   // w -> w convolutions in the activation type
+    CW c;
+    c.mfma = e.use_mfma && igemm_mfma_available() && I % 32 == 0 && O % 16 == 0;
+    size_t off = walloc((size_t)O * I * 9 * e.elt);
+    add_entry(name + ".w", {O, I, 3, 3}, 0, c.mfma ? LA_MFMA : LA_ROWMAJOR, off, O, I, 9);
+    c.w = e.img_weights + off;
+    c.b = with_bias ? bias(name + ".b", O) : nullptr;
+    return c;
+  }
+  void* aalloc(size_t elems) {
+    size_t off = e.img_act.alloc(elems * e.elt);
+    return e.img_act_base + off * (size_t)e.cfg.n_streams;
+  }
+  void afree(void* p) { e.img_act.release((size_t)((char*)p - e.img_act_base) / (size_t)e.cfg.n_streams); }
+
+  void* conv(const void* src, int C, int Hin, int Win, int Hout, int Wout, int stride, int ups, const CW& w,
+             const void* residual, int epi) {
+    Op op{};
+    op.kind = OP_IGEMM;
+    op.mfma = w.mfma;
+    op.cls = w.mfma ? PC_IGEMM_MFMA : PC_IGEMM_VALU;
+    op.ln_src_op = -1;
+    IgemmParams& g = op.g;
+    g.src1 = src; g.C1 = C; g.C2 = 0;
+    g.Hin = Hin; g.Win = Win; g.Hout = Hout; g.Wout = Wout;
+    g.ksize = 3; g.stride = stride; g.upsample = ups;
+    g.N = C; g.K = 9 * C;
+    g.W = w.w; g.bias = w.b;
+    g.residual = residual;
+    g.epilogue = epi;
+    g.splitk = 1;
+    g.out = aalloc((size_t)Hout * Wout * C);
+    op.rows_per_sample = Hout * Wout;
+    op.flops_per_row = 2.0 * Hout * Wout * (double)C * g.K;
+    ops->push_back(op);
+    return g.out;
+  }
+  void* block(const std::string& p, void* x, int C, int H, int W) {
+    CW a = convw(p + ".a", C, C, true), b = convw(p + ".b", C, C, true), c = convw(p + ".c", C, C, true);
+    void* t1 = conv(x, C, H, W, H, W, 1, 0, a, nullptr, EPI_RELU);
+    void* t2 = conv(t1, C, H, W, H, W, 1, 0, b, nullptr, EPI_RELU);
+    afree(t1);
+    void* out = conv(t2, C, H, W, H, W, 1, 0, c, x, EPI_RELU);   // ReLU(conv_c(.) + x)
+    afree(t2);
+    afree(x);
+    return out;
+  }
+  void build() {
+    const sdstream_config& c = e.cfg;
+    const int w = c.image_width, lc = c.in_channels;
+    int H = c.latent_h * 8, W = c.latent_w * 8;
+    e.img_enc_ops.clear();
+    e.img_dec_ops.clear();
+    e.img_act = PlanAllocator();
+    // ---- encoder
+    ops = &e.img_enc_ops;
+    void* x;
+    {
+      size_t woff = walloc((size_t)w * 27 * 4);
+      add_entry("enc.in.w", {w, 3, 3, 3}, 0, LA_F32, woff, w, 3, 9);
+      Op op{};
+      op.kind = OP_IMAGE_IN;
+      op.cls = PC_CONV_IN;
+      op.cw_f32 = (const float*)(e.img_weights + woff);
+      op.cb = bias("enc.in.b", w);
+      op.cH = H; op.cW = W; op.cCin = 3; op.cC0 = w;
+      op.cout_ = aalloc((size_t)H * W * w);
+      op.rows_per_sample = H * W;
+      ops->push_back(op);
+      x = op.cout_;
+    }
+    x = block("enc.0.block.0", x, w, H, W);
+    for (int s = 1; s <= 3; ++s) {
+      CW d = convw("enc." + std::to_string(s) + ".down", w, w, false);
+      void* y = conv(x, w, H, W, H / 2, W / 2, 2, 0, d, nullptr, EPI_NONE);
+      afree(x);
+      x = y;
+      H /= 2; W /= 2;
+      for (int j = 0; j < 3; ++j) x = block("enc." + std::to_string(s) + ".block." + std::to_string(j), x, w, H, W);
+    }
+    {
+      size_t woff = walloc((size_t)lc * 9 * w * e.elt);
+      add_entry("enc.out.w", {lc, w, 3, 3}, 0, LA_ROWMAJOR, woff, lc, w, 9);
+      Op op{};
+      op.kind = OP_CONV_OUT;
+      op.cls = PC_CONV_OUT;
+      op.cin = x;
+      op.cw = e.img_weights + woff;
+      op.cb = bias("enc.out.b", lc);
+      op.cH = H; op.cW = W; op.cCin = lc; op.cC0 = w;
+      op.rows_per_sample = H * W;
+      ops->push_back(op);   // cout_ (the latent) is set per call
+    }
+    afree(x);
+    // ---- decoder
+    ops = &e.img_dec_ops;
+    {
+      size_t woff = walloc((size_t)w * lc * 9 * 4);
+      add_entry("dec.in.w", {w, lc, 3, 3}, 0, LA_F32, woff, w, lc, 9);
+      Op op{};
+      op.kind = OP_CONV_IN;
+      op.cls = PC_CONV_IN;
+      op.cw_f32 = (const float*)(e.img_weights + woff);
+      op.cb = bias("dec.in.b", w);
+      op.cH = H; op.cW = W; op.cCin = lc; op.cC0 = w; op.cflags = CONV_IN_SQUASH | CONV_IN_RELU;
+      op.cout_ = aalloc((size_t)H * W * w);
+      op.rows_per_sample = H * W;
+      ops->push_back(op);   // cin (the latent) is set per call
+      x = op.cout_;
+    }
+    for (int s = 0; s < 3; ++s) {
+      for (int j = 0; j < 3; ++j) x = block("dec." + std::to_string(s) + ".block." + std::to_string(j), x, w, H, W);
+      CW u = convw("dec." + std::to_string(s) + ".up", w, w, false);
+      void* y = conv(x, w, H, W, 2 * H, 2 * W, 1, 1, u, nullptr, EPI_NONE);
+      afree(x);
+      x = y;
+      H *= 2; W *= 2;
+    }
+    x = block("dec.3.block.0", x, w, H, W);
+    {
+      size_t woff = walloc((size_t)3 * 9 * w * e.elt);
+      add_entry("dec.out.w", {3, w, 3, 3}, 0, LA_ROWMAJOR, woff, 3, w, 9);
+      Op op{};
+      op.kind = OP_IMAGE_OUT;
+      op.cls = PC_CONV_OUT;
+      op.cin = x;
+      op.cw = e.img_weights + woff;
+      op.cb = bias("dec.out.b", 3);
+      op.cH = H; op.cW = W; op.cCin = 3; op.cC0 = w;
+      op.rows_per_sample = H * W;
+      ops->push_back(op);   // img_f32 / img_u8 are set per call
+    }
+    afree(x);
   }
 };
 
@@ -798,6 +996,9 @@ int validate(const sdstream_config& c, std::string& why) {
   if (c.cfg_mode < 0 || c.cfg_mode > 3) BAD("cfg_mode %d", c.cfg_mode);
   if (c.scheduler < 0 || c.scheduler > 2) BAD("scheduler %d", c.scheduler);
   if (c.cross_frame < 0 || c.cross_frame > 1) BAD("cross_frame %d", c.cross_frame);
+  if (c.image_width < 0 || c.image_width > 512) BAD("image_width %d out of range", c.image_width);
+  if (c.image_width > 0 && c.in_channels != 4) BAD("the image stage needs 4 latent channels");
+  if (c.image_width > 0 && (long long)(27 * c.image_width + 64 * 28) * 4 > 65536) BAD("image_width %d: LDS tile too large", c.image_width);
   for (int l = 0; l < c.n_levels; ++l) {
     int ch = c.block_channels[l];
     if (ch < 1 || ch % c.norm_groups) BAD("block_channels[%d]=%d not a multiple of norm_groups", l, ch);
@@ -912,17 +1113,26 @@ void launch_op(sdstream* h, const Op& op0, int N, const int* kv_select, int xfra
       break;
     }
     case OP_CONV_IN: {
-      const sdstream_config& c = h->cfg;
       const float* x = (const float*)op0.cin;
-      if (bf) launch_conv_in<bf16_t>(x, op0.cw_f32, op0.cb, op0.cout_, N, c.in_channels, c.latent_h, c.latent_w, c.block_channels[0], s);
-      else launch_conv_in<float>(x, op0.cw_f32, op0.cb, op0.cout_, N, c.in_channels, c.latent_h, c.latent_w, c.block_channels[0], s);
+      if (bf) launch_conv_in<bf16_t>(x, op0.cw_f32, op0.cb, op0.cout_, N, op0.cCin, op0.cH, op0.cW, op0.cC0, op0.cflags, s);
+      else launch_conv_in<float>(x, op0.cw_f32, op0.cb, op0.cout_, N, op0.cCin, op0.cH, op0.cW, op0.cC0, op0.cflags, s);
       break;
     }
     case OP_CONV_OUT: {
-      const sdstream_config& c = h->cfg;
       float* out = (float*)op0.cout_;
-      if (bf) launch_conv_out<bf16_t>(op0.cin, op0.cw, op0.cb, out, N, c.in_channels, c.latent_h, c.latent_w, c.block_channels[0], s);
-      else launch_conv_out<float>(op0.cin, op0.cw, op0.cb, out, N, c.in_channels, c.latent_h, c.latent_w, c.block_channels[0], s);
+      if (bf) launch_conv_out<bf16_t>(op0.cin, op0.cw, op0.cb, out, N, op0.cCin, op0.cH, op0.cW, op0.cC0, s);
+      else launch_conv_out<float>(op0.cin, op0.cw, op0.cb, out, N, op0.cCin, op0.cH, op0.cW, op0.cC0, s);
+      break;
+    }
+    case OP_IMAGE_IN: {
+      const uint8_t* img = (const uint8_t*)op0.cin;
+      if (bf) launch_image_in<bf16_t>(img, op0.cw_f32, op0.cb, op0.cout_, N, op0.cH, op0.cW, op0.cC0, s);
+      else launch_image_in<float>(img, op0.cw_f32, op0.cb, op0.cout_, N, op0.cH, op0.cW, op0.cC0, s);
+      break;
+    }
+    case OP_IMAGE_OUT: {
+      if (bf) launch_image_out<bf16_t>(op0.cin, op0.cw, op0.cb, op0.img_f32, op0.img_u8, N, op0.cH, op0.cW, op0.cC0, s);
+      else launch_image_out<float>(op0.cin, op0.cw, op0.cb, op0.img_f32, op0.img_u8, N, op0.cH, op0.cW, op0.cC0, s);
       break;
     }
   }
@@ -1036,6 +1246,53 @@ int build_kv(sdstream* h, const float* ctx, const float* neg, hipStream_t s) {
   return SDSTREAM_OK;
 }
 
+// copies the tensors of `entries` from a host blob (manifest order, float32) into the arena at `base`, converting and
+// repacking each as its entry says; synchronous
+int load_entries(sdstream* h, const std::vector<Entry>& entries, char* base, int64_t n_params,
+                 const std::vector<BiasFix>& fixes, const void* host_blob, size_t bytes) {
+  if (bytes != (size_t)n_params * 4)
+    return fail(h, SDSTREAM_E_SHAPE, "blob has %zu bytes, the manifest needs %zu", bytes, (size_t)n_params * 4);
+  size_t max_count = 0;
+  for (const Entry& en : entries) max_count = en.count > max_count ? en.count : max_count;
+  float* stage = nullptr;
+  HIP_TRY(h, hipMalloc((void**)&stage, max_count * 4));
+  const bool bf = h->cfg.dtype == 1;
+  const float* src = (const float*)host_blob;
+  hipStream_t s = nullptr;
+  int rc = SDSTREAM_OK;
+  for (const Entry& en : entries) {
+    hipError_t er = hipMemcpy(stage, src, en.count * 4, hipMemcpyHostToDevice);
+    if (er != hipSuccess) { rc = fail(h, SDSTREAM_E_HIP, "hipMemcpy: %s", hipGetErrorString(er)); break; }
+    src += en.count;
+    void* dst = base + en.dst_off;
+    switch (en.action) {
+      case LA_F32: launch_copy_rows_f32(stage, (float*)dst, (long long)en.count, s); break;
+      case LA_ROWMAJOR:
+        if (bf) launch_repack_rowmajor<bf16_t>(stage, dst, en.O, en.I, en.taps, en.geglu, s);
+        else launch_repack_rowmajor<float>(stage, dst, en.O, en.I, en.taps, en.geglu, s);
+        break;
+      case LA_MFMA:
+        if (en.ln_fold) {
+          launch_repack_mfma(stage, dst, en.O, en.I, en.taps, en.geglu, (const float*)(base + en.ln_g), s);
+          launch_ln_fold_vectors(stage, (const float*)(base + en.ln_g), (const float*)(base + en.ln_b),
+                                 (float*)(base + en.ln_wsum), (float*)(base + en.ln_lnb), en.O, en.I, en.geglu, s);
+        } else {
+          launch_repack_mfma(stage, dst, en.O, en.I, en.taps, en.geglu, nullptr, s);
+        }
+        break;
+      case LA_BIAS_PERM: launch_permute_bias(stage, (float*)dst, en.O, en.geglu, s); break;
+    }
+    er = hipDeviceSynchronize();
+    if (er != hipSuccess) { rc = fail(h, SDSTREAM_E_HIP, "repack: %s", hipGetErrorString(er)); break; }
+  }
+  hipFree(stage);
+  if (rc) return rc;
+  for (const BiasFix& f : fixes)   // bias + shift-times-weights of a folded LayerNorm, once both are there
+    launch_add_f32((float*)(base + f.lnb), (const float*)(base + f.bias), f.n, s);
+  HIP_TRY(h, hipDeviceSynchronize());
+  return SDSTREAM_OK;
+}
+
 uint64_t splitmix64_mix(uint64_t z) {
   z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
   z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
@@ -1079,6 +1336,13 @@ int sdstream_create(const sdstream_config* cfg, sdstream_t** out) {
   }
   h->n_params = 0;
   for (const Entry& en : h->manifest) h->n_params += (int64_t)en.count;
+  if (cfg->image_width > 0) {
+    ImageBuilder ib(*h, true);
+    ib.build();
+    h->img_weight_bytes = ib.wbytes;
+    h->img_act_bytes = h->img_act.peak * (size_t)cfg->n_streams;
+    for (const Entry& en : h->img_manifest) h->img_n_params += (int64_t)en.count;
+  }
   hipError_t e1 = hipMalloc((void**)&h->weights, h->weight_bytes);
   hipError_t e2 = e1 == hipSuccess ? hipMalloc((void**)&h->persist, h->persist_bytes) : e1;
   hipError_t e3 = e2 == hipSuccess ? hipMalloc((void**)&h->act_base, h->act_bytes ? h->act_bytes : 256) : e2;
@@ -1091,6 +1355,18 @@ int sdstream_create(const sdstream_config* cfg, sdstream_t** out) {
   if (hipMemset(h->persist, 0, h->persist_bytes) != hipSuccess) {
     sdstream_destroy(h);
     return fail(nullptr, SDSTREAM_E_HIP, "hipMemset failed");
+  }
+  if (cfg->image_width > 0) {
+    hipError_t i1 = hipMalloc((void**)&h->img_weights, h->img_weight_bytes);
+    hipError_t i2 = i1 == hipSuccess ? hipMalloc((void**)&h->img_act_base, h->img_act_bytes) : i1;
+    if (i2 != hipSuccess) {
+      int code = fail(nullptr, i2 == hipErrorOutOfMemory ? SDSTREAM_E_NOMEM : SDSTREAM_E_HIP, "hipMalloc: %s",
+                      hipGetErrorString(i2));
+      sdstream_destroy(h);
+      return code;
+    }
+    ImageBuilder ib(*h, false);
+    ib.build();
   }
   // pass 2: real pointers
   {
@@ -1106,6 +1382,9 @@ void sdstream_destroy(sdstream_t* h) {
   if (!h) return;
   hipDeviceSynchronize();
   for (auto& kv : h->graphs) hipGraphExecDestroy(kv.second);
+  for (auto& ig : h->img_graph) if (ig.exec) hipGraphExecDestroy(ig.exec);
+  if (h->img_weights) hipFree(h->img_weights);
+  if (h->img_act_base) hipFree(h->img_act_base);
   if (h->cap_stream) hipStreamDestroy(h->cap_stream);
   for (auto& r : h->prof_pending) { hipEventDestroy(r.a); hipEventDestroy(r.b); }
   if (h->weights) hipFree(h->weights);
@@ -1140,50 +1419,40 @@ int sdstream_manifest_entry(const sdstream_t* h, int32_t index, char* name, size
 
 int sdstream_load_weights(sdstream_t* h, const void* host_blob, size_t bytes) {
   if (!h || !host_blob) return h ? fail(h, SDSTREAM_E_INVALID_ARG, "null blob") : SDSTREAM_E_INVALID_ARG;
-  if (bytes != (size_t)h->n_params * 4)
-    return fail(h, SDSTREAM_E_SHAPE, "blob has %zu bytes, the manifest needs %zu", bytes, (size_t)h->n_params * 4);
-  size_t max_count = 0;
-  for (const Entry& en : h->manifest) max_count = en.count > max_count ? en.count : max_count;
-  float* stage = nullptr;
-  HIP_TRY(h, hipMalloc((void**)&stage, max_count * 4));
-  const bool bf = h->cfg.dtype == 1;
-  const float* src = (const float*)host_blob;
-  hipStream_t s = nullptr;
-  int rc = SDSTREAM_OK;
-  for (const Entry& en : h->manifest) {
-    hipError_t er = hipMemcpy(stage, src, en.count * 4, hipMemcpyHostToDevice);
-    if (er != hipSuccess) { rc = fail(h, SDSTREAM_E_HIP, "hipMemcpy: %s", hipGetErrorString(er)); break; }
-    src += en.count;
-    void* dst = h->weights + en.dst_off;
-    switch (en.action) {
-      case LA_F32: launch_copy_rows_f32(stage, (float*)dst, (long long)en.count, s); break;
-      case LA_ROWMAJOR:
-        if (bf) launch_repack_rowmajor<bf16_t>(stage, dst, en.O, en.I, en.taps, en.geglu, s);
-        else launch_repack_rowmajor<float>(stage, dst, en.O, en.I, en.taps, en.geglu, s);
-        break;
-      case LA_MFMA:
-        if (en.ln_fold) {
-          launch_repack_mfma(stage, dst, en.O, en.I, en.taps, en.geglu, (const float*)(h->weights + en.ln_g), s);
-          launch_ln_fold_vectors(stage, (const float*)(h->weights + en.ln_g), (const float*)(h->weights + en.ln_b),
-                                 (float*)(h->weights + en.ln_wsum), (float*)(h->weights + en.ln_lnb), en.O, en.I,
-                                 en.geglu, s);
-        } else {
-          launch_repack_mfma(stage, dst, en.O, en.I, en.taps, en.geglu, nullptr, s);
-        }
-        break;
-      case LA_BIAS_PERM: launch_permute_bias(stage, (float*)dst, en.O, en.geglu, s); break;
-    }
-    er = hipDeviceSynchronize();
-    if (er != hipSuccess) { rc = fail(h, SDSTREAM_E_HIP, "repack: %s", hipGetErrorString(er)); break; }
-  }
-  hipFree(stage);
+  int rc = load_entries(h, h->manifest, h->weights, h->n_params, h->bias_fixes, host_blob, bytes);
   if (rc) return rc;
-  for (const BiasFix& f : h->bias_fixes)   // bias + shift-times-weights of a folded LayerNorm, once both are there
-    launch_add_f32((float*)(h->weights + f.lnb), (const float*)(h->weights + f.bias), f.n, s);
-  HIP_TRY(h, hipDeviceSynchronize());
   h->weights_loaded = true;
   h->temb_cached.clear();
   h->kv_valid = false;
+  return SDSTREAM_OK;
+}
+
+int64_t sdstream_image_param_count(const sdstream_t* h) { return h ? h->img_n_params : 0; }
+int32_t sdstream_image_manifest_size(const sdstream_t* h) { return h ? (int32_t)h->img_manifest.size() : 0; }
+
+int sdstream_image_manifest_entry(const sdstream_t* h, int32_t index, char* name, size_t name_cap, int32_t shape[4],
+                                  int32_t* ndim, int32_t* kind) {
+  if (!h) return SDSTREAM_E_INVALID_ARG;
+  sdstream* hm = const_cast<sdstream*>(h);
+  if (index < 0 || index >= (int32_t)h->img_manifest.size()) return fail(hm, SDSTREAM_E_INVALID_ARG, "index out of range");
+  const Entry& en = h->img_manifest[index];
+  if (name && name_cap) {
+    strncpy(name, en.name.c_str(), name_cap - 1);
+    name[name_cap - 1] = 0;
+  }
+  if (shape) for (int i = 0; i < 4; ++i) shape[i] = en.shape[i];
+  if (ndim) *ndim = en.ndim;
+  if (kind) *kind = en.kind;
+  return SDSTREAM_OK;
+}
+
+int sdstream_load_image_weights(sdstream_t* h, const void* host_blob, size_t bytes) {
+  if (!h || !host_blob) return h ? fail(h, SDSTREAM_E_INVALID_ARG, "null blob") : SDSTREAM_E_INVALID_ARG;
+  if (h->cfg.image_width <= 0) return fail(h, SDSTREAM_E_NOT_READY, "this engine was created without an image stage");
+  static const std::vector<BiasFix> none;
+  int rc = load_entries(h, h->img_manifest, h->img_weights, h->img_n_params, none, host_blob, bytes);
+  if (rc) return rc;
+  h->img_weights_loaded = true;
   return SDSTREAM_OK;
 }
 
@@ -1240,10 +1509,13 @@ int sdstream_unet_forward(sdstream_t* h, const float* x, const int32_t* t, const
   return run_unet(h, x, eps_out, n, (const int*)(h->persist + h->off_sel_zero), false, s);
 }
 
-int sdstream_step(sdstream_t* h, const float* x0_in, const float* context, const float* neg_context,
-                  uint64_t context_epoch, const int32_t* timesteps, float gamma, float delta, float* out_latent,
-                  int32_t* out_valid, void* hip_stream) {
-  if (!h) return SDSTREAM_E_INVALID_ARG;
+}  // extern "C"
+
+namespace {
+// everything of a step that comes before its launches: argument checks, schedule constants and queue reset on new
+// timesteps, time-embedding biases, the prompt's keys / values; fills the parameter block of head and tail
+int step_prepare(sdstream* h, const float* x0_in, const float* context, const float* neg_context, uint64_t context_epoch,
+                 const int32_t* timesteps, float gamma, float delta, float* out_latent, hipStream_t s, StreamParams* pp) {
   const sdstream_config& c = h->cfg;
   if (!x0_in || !context || !timesteps || !out_latent) return fail(h, SDSTREAM_E_INVALID_ARG, "null argument");
   if (!h->weights_loaded) return fail(h, SDSTREAM_E_NOT_READY, "weights not loaded");
@@ -1256,7 +1528,6 @@ int sdstream_step(sdstream_t* h, const float* x0_in, const float* context, const
       return fail(h, SDSTREAM_E_INVALID_ARG, "timestep %d outside [0,999]", timesteps[i]);
     if (i && timesteps[i] >= timesteps[i - 1]) return fail(h, SDSTREAM_E_INVALID_ARG, "timesteps must strictly decrease");
   }
-  hipStream_t s = (hipStream_t)hip_stream;
   std::vector<int> ts(timesteps, timesteps + n);
   const int rows = h->max_batch;
   if (ts != h->timesteps) {
@@ -1292,7 +1563,7 @@ int sdstream_step(sdstream_t* h, const float* x0_in, const float* context, const
     h->kv_epoch = context_epoch;
   }
 
-  StreamParams p;
+  StreamParams& p = *pp;
   p.S = S; p.n = n; p.E = h->E; p.mode = c.cfg_mode; p.scheduler = c.scheduler;
   p.gamma = gamma; p.delta = delta;
   p.a = (const float*)(h->persist + h->off_ab);
@@ -1307,7 +1578,21 @@ int sdstream_step(sdstream_t* h, const float* x0_in, const float* context, const
   p.rnext = (float*)(h->persist + h->off_r[h->cur ^ 1]);
   p.eps = (const float*)(h->persist + h->off_eps);
   p.out = out_latent;
+  return SDSTREAM_OK;
+}
+}  // namespace
 
+extern "C" {
+
+int sdstream_step(sdstream_t* h, const float* x0_in, const float* context, const float* neg_context,
+                  uint64_t context_epoch, const int32_t* timesteps, float gamma, float delta, float* out_latent,
+                  int32_t* out_valid, void* hip_stream) {
+  if (!h) return SDSTREAM_E_INVALID_ARG;
+  hipStream_t s = (hipStream_t)hip_stream;
+  StreamParams p;
+  int rc = step_prepare(h, x0_in, context, neg_context, context_epoch, timesteps, gamma, delta, out_latent, s, &p);
+  if (rc) return rc;
+  const int n = h->cfg.n_denoise, S = h->cfg.n_streams, rows = h->max_batch;
   const double head_bytes = (double)S * h->E * 4 * 3, tail_bytes = (double)S * n * h->E * 4 * 5;
   if (h->profiling) { rc = prof_begin(h, PC_STREAM_HEAD, 0, head_bytes, s); if (rc) return rc; }
   launch_stream_head(p, s);
@@ -1317,6 +1602,91 @@ int sdstream_step(sdstream_t* h, const float* x0_in, const float* context, const
   if (h->profiling) { rc = prof_begin(h, PC_STREAM_TAIL, 0, tail_bytes, s); if (rc) return rc; }
   launch_stream_tail(p, s);
   if (h->profiling) { rc = prof_end(h, s); if (rc) return rc; }
+  HIP_TRY(h, hipGetLastError());
+  if (out_valid) *out_valid = h->calls >= n - 1 ? 1 : 0;
+  h->calls++;
+  h->cur ^= 1;
+  return SDSTREAM_OK;
+}
+
+int sdstream_encode(sdstream_t* h, const uint8_t* image, float* latent_out, void* hip_stream) {
+  if (!h) return SDSTREAM_E_INVALID_ARG;
+  if (!image || !latent_out) return fail(h, SDSTREAM_E_INVALID_ARG, "null argument");
+  if (!h->img_weights_loaded) return fail(h, SDSTREAM_E_NOT_READY, "image-stage weights not loaded");
+  hipStream_t s = (hipStream_t)hip_stream;
+  h->img_enc_ops.front().cin = image;
+  h->img_enc_ops.back().cout_ = latent_out;
+  for (const Op& op : h->img_enc_ops) launch_op(h, op, h->cfg.n_streams, nullptr, 0, s);
+  HIP_TRY(h, hipGetLastError());
+  return SDSTREAM_OK;
+}
+
+int sdstream_decode(sdstream_t* h, const float* latent, uint8_t* image_out, float* image_f32_out, void* hip_stream) {
+  if (!h) return SDSTREAM_E_INVALID_ARG;
+  if (!latent || (!image_out && !image_f32_out)) return fail(h, SDSTREAM_E_INVALID_ARG, "null argument");
+  if (!h->img_weights_loaded) return fail(h, SDSTREAM_E_NOT_READY, "image-stage weights not loaded");
+  hipStream_t s = (hipStream_t)hip_stream;
+  h->img_dec_ops.front().cin = latent;
+  h->img_dec_ops.back().img_u8 = image_out;
+  h->img_dec_ops.back().img_f32 = image_f32_out;
+  for (const Op& op : h->img_dec_ops) launch_op(h, op, h->cfg.n_streams, nullptr, 0, s);
+  HIP_TRY(h, hipGetLastError());
+  return SDSTREAM_OK;
+}
+
+int sdstream_step_image(sdstream_t* h, const uint8_t* frame, const float* context, const float* neg_context,
+                        uint64_t context_epoch, const int32_t* timesteps, float gamma, float delta, uint8_t* image_out,
+                        int32_t* out_valid, void* hip_stream) {
+  if (!h) return SDSTREAM_E_INVALID_ARG;
+  if (!frame || !image_out) return fail(h, SDSTREAM_E_INVALID_ARG, "null argument");
+  if (!h->img_weights_loaded) return fail(h, SDSTREAM_E_NOT_READY, "image-stage weights not loaded");
+  hipStream_t s = (hipStream_t)hip_stream;
+  float* lat_in = (float*)(h->persist + h->off_img_lat_in);
+  float* lat_out = (float*)(h->persist + h->off_img_lat_out);
+  StreamParams p;
+  int rc = step_prepare(h, lat_in, context, neg_context, context_epoch, timesteps, gamma, delta, lat_out, s, &p);
+  if (rc) return rc;
+  const int n = h->cfg.n_denoise, S = h->cfg.n_streams, rows = h->max_batch;
+  h->img_enc_ops.front().cin = frame;
+  h->img_enc_ops.back().cout_ = lat_in;
+  h->img_dec_ops.front().cin = lat_out;
+  h->img_dec_ops.back().img_u8 = image_out;
+  h->img_dec_ops.back().img_f32 = nullptr;
+  h->ops.front().cin = p.xcur;
+  h->ops.back().cout_ = (float*)(h->persist + h->off_eps);
+  const int* sel = (const int*)(h->persist + h->off_sel_step);
+  const int xframe_rows = (h->cfg.cfg_mode == SDSTREAM_CFG_FULL ? 2 : 1) * S * n;
+  auto launch_all = [&](hipStream_t st) {   // image -> latent -> one Stream Batch step -> latent -> image
+    for (const Op& op : h->img_enc_ops) launch_op(h, op, S, nullptr, 0, st);
+    launch_stream_head(p, st);
+    for (const Op& op : h->ops) launch_op(h, op, rows, sel, xframe_rows, st);
+    launch_stream_tail(p, st);
+    for (const Op& op : h->img_dec_ops) launch_op(h, op, S, nullptr, 0, st);
+  };
+  if (h->graph_enabled && !h->profiling) {
+    // One graph per queue buffer.  What a captured launch bakes in besides the engine's own buffers - the caller's two
+    // image pointers and the guidance scalars - is remembered with the graph; a call that differs captures again, so a
+    // caller that hands over the same device buffers every frame replays one graph per frame.
+    sdstream::ImageGraph& ig = h->img_graph[h->cur];
+    if (ig.exec && (ig.frame != frame || ig.image != image_out || ig.gamma != gamma || ig.delta != delta)) {
+      hipGraphExecDestroy(ig.exec);
+      ig.exec = nullptr;
+    }
+    if (!ig.exec) {
+      if (!h->cap_stream) HIP_TRY(h, hipStreamCreateWithFlags(&h->cap_stream, hipStreamNonBlocking));
+      HIP_TRY(h, hipStreamBeginCapture(h->cap_stream, hipStreamCaptureModeThreadLocal));
+      launch_all(h->cap_stream);
+      hipGraph_t gph = nullptr;
+      HIP_TRY(h, hipStreamEndCapture(h->cap_stream, &gph));
+      hipError_t er = hipGraphInstantiate(&ig.exec, gph, nullptr, nullptr, 0);
+      hipGraphDestroy(gph);
+      if (er != hipSuccess) { ig.exec = nullptr; return fail(h, SDSTREAM_E_HIP, "hipGraphInstantiate: %s", hipGetErrorString(er)); }
+      ig.frame = frame; ig.image = image_out; ig.gamma = gamma; ig.delta = delta;
+    }
+    HIP_TRY(h, hipGraphLaunch(ig.exec, s));
+  } else {
+    launch_all(s);
+  }
   HIP_TRY(h, hipGetLastError());
   if (out_valid) *out_valid = h->calls >= n - 1 ? 1 : 0;
   h->calls++;

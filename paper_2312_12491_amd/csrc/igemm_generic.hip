@@ -111,6 +111,7 @@ __global__ __launch_bounds__(256) void igemm_generic_kernel(IgemmParams p) {
         float x = v[j];
         if (p.epilogue == EPI_SILU) x = silu(x);
         if (res) x += to_f32<T>(res[(long long)m * Nout + n]);
+        if (p.epilogue == EPI_RELU) x = fmaxf(x, 0.f);
         out[(long long)m * Nout + n] = from_f32<T>(x);
       }
     }

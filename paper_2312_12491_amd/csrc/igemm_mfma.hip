@@ -136,7 +136,7 @@ __device__ __forceinline__ void epilogue_load(const IgemmParams& p, EpilogueIn<M
     in.rbv[nt] = *(const f32x4*)rsrc;
     in.wsv[nt] = *(const f32x4*)(p.ln_wsum ? p.ln_wsum + n : (const float*)p.zeros);
   }
-  if (res && p.epilogue != EPI_GEGLU) {
+  if (res && p.epilogue != EPI_GEGLU) {   // (plain and ReLU epilogues)
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       const int m = max(min(mbase + mt * 16 + (lane & 15), p.M - 1), 0);
@@ -221,6 +221,10 @@ __device__ __forceinline__ void epilogue_store(const IgemmParams& p, f32x4 (&acc
       if (has_res) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) x[v] += (float)in.rv[mt][nt][v];
+      }
+      if (p.epilogue == EPI_RELU) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) x[v] = fmaxf(x[v], 0.f);
       }
       bf16x4 o;
 #pragma unroll

@@ -11,7 +11,7 @@ constexpr int CI_PIX = 64;
 template <typename T>
 __global__ __launch_bounds__(256) void conv_in_kernel(const float* __restrict__ x, const float* __restrict__ w,
                                                       const float* __restrict__ b, T* __restrict__ out, int N, int Cin,
-                                                      int H, int W, int C0) {
+                                                      int H, int W, int C0, int flags) {
   extern __shared__ float sm[];
   const int K = Cin * 9;
   float* wt = sm;               // [K][C0]
@@ -32,6 +32,7 @@ __global__ __launch_bounds__(256) void conv_in_kernel(const float* __restrict__ 
       int iy = yy + t / 3 - 1, ix = xx + t % 3 - 1;
       if (iy >= 0 && iy < H && ix >= 0 && ix < W) v = x[(((long long)n * Cin + ci) * H + iy) * W + ix];
     }
+    if (flags & CONV_IN_SQUASH) v = 3.0f * tanhf(v * (1.0f / 3.0f));
     patch[i] = v;
   }
   __syncthreads();
@@ -40,6 +41,7 @@ __global__ __launch_bounds__(256) void conv_in_kernel(const float* __restrict__ 
     if (pix0 + p >= total_pix) break;
     float acc = b[co];
     for (int k = 0; k < K; ++k) acc = fmaf(wt[k * C0 + co], patch[p * K + k], acc);
+    if (flags & CONV_IN_RELU) acc = fmaxf(acc, 0.f);
     out[(pix0 + p) * C0 + co] = from_f32<T>(acc);
   }
 }
@@ -76,7 +78,7 @@ __global__ __launch_bounds__(256) void conv_out_kernel(const T* __restrict__ x, 
 constexpr int CIF_PIX = 32;
 __global__ __launch_bounds__(1024) void conv_in4_bf16_kernel(const float* __restrict__ x, const float* __restrict__ w,
                                                              const float* __restrict__ b, bf16_t* __restrict__ out, int N,
-                                                             int H, int W, int C0) {
+                                                             int H, int W, int C0, int flags) {
   __shared__ __attribute__((aligned(16))) float patch[CIF_PIX * 36];
   const long long total_pix = (long long)N * H * W;
   const long long pix0 = (long long)blockIdx.x * CIF_PIX;
@@ -90,6 +92,7 @@ __global__ __launch_bounds__(1024) void conv_in4_bf16_kernel(const float* __rest
       const int iy = yy + t / 3 - 1, ix = xx + t % 3 - 1;
       if (iy >= 0 && iy < H && ix >= 0 && ix < W) v = x[(((long long)n * 4 + ci) * H + iy) * W + ix];
     }
+    if (flags & CONV_IN_SQUASH) v = 3.0f * tanhf(v * (1.0f / 3.0f));
     patch[i] = v;
   }
   __syncthreads();
@@ -111,6 +114,7 @@ __global__ __launch_bounds__(1024) void conv_in4_bf16_kernel(const float* __rest
       acc = fmaf(wv[j].z, v.z, acc);
       acc = fmaf(wv[j].w, v.w, acc);
     }
+    if (flags & CONV_IN_RELU) acc = fmaxf(acc, 0.f);
     out[(pix0 + p) * C0 + co] = (bf16_t)acc;
   }
 }
@@ -380,20 +384,20 @@ inline unsigned blocks_for(long long n, int per = 256, long long cap = 1 << 20) 
 
 template <typename T>
 void launch_conv_in(const float* x, const float* w, const float* b, void* out, int N, int Cin, int H, int W, int C0,
-                    hipStream_t s) {
+                    int flags, hipStream_t s) {
   long long pix = (long long)N * H * W;
   if (sizeof(T) == 2 && Cin == 4 && C0 <= 1024) {
     const int threads = (C0 + 63) / 64 * 64;
     hipLaunchKernelGGL(conv_in4_bf16_kernel, dim3((unsigned)((pix + CIF_PIX - 1) / CIF_PIX)), dim3(threads), 0, s, x, w,
-                       b, (bf16_t*)out, N, H, W, C0);
+                       b, (bf16_t*)out, N, H, W, C0, flags);
     return;
   }
   size_t lds = (size_t)(Cin * 9 * C0 + CI_PIX * Cin * 9) * sizeof(float);
   hipLaunchKernelGGL(conv_in_kernel<T>, dim3((unsigned)((pix + CI_PIX - 1) / CI_PIX)), dim3(256), lds, s, x, w, b,
-                     (T*)out, N, Cin, H, W, C0);
+                     (T*)out, N, Cin, H, W, C0, flags);
 }
-template void launch_conv_in<float>(const float*, const float*, const float*, void*, int, int, int, int, int, hipStream_t);
-template void launch_conv_in<bf16_t>(const float*, const float*, const float*, void*, int, int, int, int, int, hipStream_t);
+template void launch_conv_in<float>(const float*, const float*, const float*, void*, int, int, int, int, int, int, hipStream_t);
+template void launch_conv_in<bf16_t>(const float*, const float*, const float*, void*, int, int, int, int, int, int, hipStream_t);
 
 template <typename T>
 void launch_conv_out(const void* x, const void* w, const float* b, float* out, int N, int Cout, int H, int W, int C0,

@@ -7,6 +7,8 @@ tests compare against the stored arrays:
   the three guidance modes;  config 5: first 5 frames of stream 0 (2 valid outputs);  plus one raw eps row
   (t = 999) per U-Net shape;  "3x": config 3 with Stream Batch cross-frame attention (Sec. 3.2), first 5 frames
   (2 valid outputs), into config3_xframe.npz.
+  "img": the latent <-> image stage at width 64 and 512 x 512: the latent of one seeded image and the image of one
+  seeded latent (float16 copy of the float image plus the u8 image), into image64.npz.
 Usage: python tests/golden/make_golden.py [config ...]
 """
 import os
@@ -50,6 +52,25 @@ def run(c: int, cross_frame: bool = False):
     np.savez_compressed(os.path.join(HERE, f"config{c}_xframe.npz" if cross_frame else f"config{c}.npz"), **out)
 
 
+def run_image():
+    from oracle import image as I
+    from workloads import IMAGE_STAGE, image_frames, normal
+    st = IMAGE_STAGE
+    t0 = time.time()
+    P = I.unpack(make_weights(I.manifest(st["width"]), st["seeds"]["weights"], st["init"], True), st["width"])
+    img = image_frames(st["seeds"]["images"], 1, 1, 512, 512)[0, 0]
+    lat = I.encode(P, img)
+    print(f"image stage: encoded ({time.time() - t0:.0f} s)", flush=True)
+    z = normal(st["seeds"]["latents"], "latent", (4, 64, 64), 1.5)
+    dec = I.decode(P, torch.as_tensor(z))
+    print(f"image stage: decoded ({time.time() - t0:.0f} s)", flush=True)
+    np.savez_compressed(os.path.join(HERE, "image64.npz"), latent=lat.numpy().astype(np.float32),
+                        image_f16=dec.numpy().astype(np.float16), image_u8=I.to_u8(dec))
+
+
 if __name__ == "__main__":
-    for a in (sys.argv[1:] or ["2", "3", "4", "5", "3x"]):
-        run(int(a.rstrip("x")), a.endswith("x"))
+    for a in (sys.argv[1:] or ["2", "3", "4", "5", "3x", "img"]):
+        if a == "img":
+            run_image()
+        else:
+            run(int(a.rstrip("x")), a.endswith("x"))

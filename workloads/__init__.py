@@ -7,6 +7,8 @@ binding.
 """
 from .synth import (  # noqa: F401
     CONFIGS,
+    IMAGE_STAGE,
+    image_frames,
     MINI_CONFIGS,
     normal,
     make_weights,

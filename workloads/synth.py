@@ -142,6 +142,18 @@ def stream_inputs(cfg: dict, n_frames: int) -> dict:
     )
 
 
+IMAGE_STAGE = dict(width=64, init="fanin", seeds=dict(weights=8000, images=8100, latents=8200))
+
+
+def image_frames(seed: int, n_frames: int, n_streams: int, h: int, w: int) -> np.ndarray:
+    """u8 [n_frames, n_streams, h, w, 3] stand-ins for camera frames: i.i.d. uniform pixels blurred 3x3 (neighbouring
+    pixels correlate, as in photographs), each frame drawn on its own."""
+    a = _rng(seed, f"images{h}x{w}").integers(0, 256, size=(n_frames, n_streams, h + 2, w + 2, 3)).astype(np.float32)
+    b = sum(a[:, :, i:i + h, j:j + w] for i in range(3) for j in range(3)) / 9.0
+    lo, hi = b.min(), b.max()
+    return np.clip(np.rint((b - lo) / (hi - lo) * 255.0), 0, 255).astype(np.uint8)
+
+
 def ssf_frames(seed: int, n_frames: int, h: int, w: int, static_run: int = 12, perturbed_run: int = 8,
                sigmas: Sequence[float] = (10.0, 20.0, 30.0, 60.0)) -> Iterator[np.ndarray]:
     """Synthetic u8 H×W×3 frame sequence: runs of exact repeats alternate with Gaussian-perturbed runs.
