@@ -57,6 +57,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=3)
+    ap.add_argument("--image-stage", action="store_true",
+                    help="also time the step with its boundary at the u8 image (tiny autoencoder around the U-Net): "
+                         "adds an `image_stage` object to the line; the headline value stays the latent-boundary step")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (reference point for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -68,7 +71,7 @@ def main():
     import numpy as np
     import torch
     import paper_2312_12491_amd as sd
-    from workloads import CONFIGS, make_weights, normal, stream_inputs
+    from workloads import CONFIGS, IMAGE_STAGE, image_frames, make_weights, normal, stream_inputs
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
@@ -170,6 +173,43 @@ def main():
                         "kind": "oracle", "sample": f"one U-Net row of the {rows}-row step (float64), "
                         f"{t_row:.1f} s, scaled to {rows} rows; the elementwise tail is negligible"}
 
+    image_stage = None
+    if args.image_stage:
+        eng.close()
+        icfg = sd.config_from_dict(wl["unet"], wl["latent"], wl["dtype"], n, S, mode, 0, int(args.cross_frame),
+                                   IMAGE_STAGE["width"])
+        eng = sd.Engine(icfg)
+        eng.load_weights(blob)
+        eng.load_image_weights(make_weights(eng.image_manifest(), IMAGE_STAGE["seeds"]["weights"], IMAGE_STAGE["init"],
+                                            wl["dtype"] == "bf16"))
+        eng.set_noise(inp["noise"])
+        H, W = 8 * wl["latent"][0], 8 * wl["latent"][1]
+        frames = torch.as_tensor(image_frames(IMAGE_STAGE["seeds"]["images"], 2, S, H, W)).cuda()
+        img_out = torch.empty_like(frames[0])
+        lat = torch.empty(S, 4, *wl["latent"], device="cuda")
+
+        def timed(fn, reps):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t) / reps * 1e3
+        ms_img_step = timed(lambda: eng.step_image(frames[0], ctx, neg, 1, ts, gamma, delta, img_out), args.steps)
+        ms_enc = timed(lambda: eng.encode(frames[0], lat), args.steps)
+        ms_dec = timed(lambda: eng.decode(lat, img_out, None), args.steps)
+        gf = 1e-9 * S * H * W * (2 * 27 * 64 + 2 * 64 * 27)   # first / last convolutions
+        per_px = 2.0 * 9 * 64 * 64                            # one 64 -> 64 convolution per output pixel
+        px = [H * W / 4 ** k for k in range(4)]
+        enc_gf = 1e-9 * S * per_px * (3 * px[0] + 10 * (px[1] + px[2] + px[3])) + 1e-9 * S * px[3] * 2 * 9 * 64 * 4
+        dec_gf = 1e-9 * S * per_px * (9 * px[3] + 10 * (px[2] + px[1]) + 4 * px[0]) + 1e-9 * S * px[3] * 2 * 9 * 64 * 4
+        image_stage = {"workload": f"{S} image(s) {H}x{W}x3 u8 per step, autoencoder width {IMAGE_STAGE['width']}",
+                       "step_image_ms": ms_img_step, "frames_per_s": S / (ms_img_step * 1e-3),
+                       "encode_ms": ms_enc, "decode_ms": ms_dec,
+                       "encode_tflops": (enc_gf + gf / 2) / ms_enc, "decode_tflops": (dec_gf + gf / 2) / ms_dec}
+
     line = {
         "metric": "denoised frames/sec (Stream Batch step)", "value": fps, "unit": "frames/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
@@ -181,6 +221,7 @@ def main():
         "unet_step_ms": ms_per_step, "step_tflop": step_flops / 1e12, "mfma_util": util,
         "peak_assumed_tflops": PEAK_BF16_TFLOPS, "mfma_only_kernel_tflops": mfma_ceiling,
         "roofline": roofline, "kernel_classes": classes, "cpu_baseline": cpu_baseline,
+        "image_stage": image_stage,
         "context": "paper: 91.07 fps whole pipeline on one RTX 4090 (other hardware, includes VAE): not a target",
     }
     print(json.dumps(line))

@@ -996,7 +996,7 @@ int validate(const sdstream_config& c, std::string& why) {
   if (c.cfg_mode < 0 || c.cfg_mode > 3) BAD("cfg_mode %d", c.cfg_mode);
   if (c.scheduler < 0 || c.scheduler > 2) BAD("scheduler %d", c.scheduler);
   if (c.cross_frame < 0 || c.cross_frame > 1) BAD("cross_frame %d", c.cross_frame);
-  if (c.image_width < 0 || c.image_width > 512) BAD("image_width %d out of range", c.image_width);
+  if (c.image_width < 0 || c.image_width > 256) BAD("image_width %d out of range", c.image_width);
   if (c.image_width > 0 && c.in_channels != 4) BAD("the image stage needs 4 latent channels");
   if (c.image_width > 0 && (long long)(27 * c.image_width + 64 * 28) * 4 > 65536) BAD("image_width %d: LDS tile too large", c.image_width);
   for (int l = 0; l < c.n_levels; ++l) {

@@ -5,8 +5,9 @@
 
 namespace {
 
-// u8 image [N][H][W][3] -> T NHWC [N*H*W][C0]: x / 255, 3x3, pad 1, + bias.  A block computes 64 pixels x all
-// output channels; the 27-value patches and the transposed weights sit in LDS.
+// u8 image [N][H][W][3] -> T NHWC [N*H*W][C0]: x / 255, 3x3, pad 1, + bias.  A block owns 64 pixels; their
+// 27-value patches and the transposed weights sit in LDS.  A lane owns an output channel with its 27 weights in
+// registers and a wave walks 16 of the pixels: patch values are LDS broadcasts, stores are whole pixel rows.
 constexpr int II_PIX = 64;
 template <typename T>
 __global__ __launch_bounds__(256) void image_in_kernel(const uint8_t* __restrict__ img, const float* __restrict__ w,
@@ -35,13 +36,19 @@ __global__ __launch_bounds__(256) void image_in_kernel(const uint8_t* __restrict
     patch[p * 28 + k] = v;
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < II_PIX * C0; i += 256) {
-    const int p = i / C0, co = i - p * C0;
-    if (pix0 + p >= total_pix) break;
-    float acc = b[co];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int co = lane; co < C0; co += 64) {
+    float wr[27];
 #pragma unroll
-    for (int k = 0; k < 27; ++k) acc = fmaf(wt[k * C0 + co], patch[p * 28 + k], acc);
-    out[(pix0 + p) * C0 + co] = from_f32<T>(acc);
+    for (int k = 0; k < 27; ++k) wr[k] = wt[k * C0 + co];
+    const float bias = b[co];
+    for (int p = wave; p < II_PIX; p += 4) {
+      if (pix0 + p >= total_pix) break;
+      float acc = bias;
+#pragma unroll
+      for (int k = 0; k < 27; ++k) acc = fmaf(wr[k], patch[p * 28 + k], acc);
+      out[(pix0 + p) * C0 + co] = from_f32<T>(acc);
+    }
   }
 }
 
@@ -68,16 +75,15 @@ __device__ __forceinline__ void load8(const float* p, float (&v)[8], bool aligne
 
 // T NHWC [N*H*W][C0] -> 3 channels: 3x3, pad 1, + bias, clamp to [0,1]; written as float NCHW [N][3][H][W] and / or
 // as u8 HWC [N][H][W][3] (round(255 v), half to even).  A thread owns a pixel; the 3 x 9 x C0 weights sit in LDS as
-// float in [tap][c][3] order.
+// float4 per (tap, input channel).  (C0 / 8 lanes per pixel, one 16-byte chunk of each tap per lane and a shuffle sum,
+// makes the global loads contiguous but was three times slower at 512 x 512: 254 us against 82 us.)
 template <typename T>
 __global__ __launch_bounds__(256) void image_out_kernel(const T* __restrict__ x, const T* __restrict__ w,
                                                         const float* __restrict__ b, float* __restrict__ out_f32,
                                                         uint8_t* __restrict__ out_u8, int N, int H, int W, int C0) {
-  extern __shared__ float wl[];   // [9][C0][3]
-  for (int i = threadIdx.x; i < 27 * C0; i += 256) {
-    const int co = i / (9 * C0), r = i - co * 9 * C0;   // w is [co][tap][c]
-    const int tap = r / C0, c = r - tap * C0;
-    wl[(tap * C0 + c) * 3 + co] = to_f32<T>(w[i]);
+  extern __shared__ float4 wl[];   // [9][C0]: the three output channels' weights of one (tap, input channel), padded to 16 bytes
+  for (int i = threadIdx.x; i < 9 * C0; i += 256) {   // w is [co][tap][c]
+    wl[i] = make_float4(to_f32<T>(w[i]), to_f32<T>(w[9 * C0 + i]), to_f32<T>(w[18 * C0 + i]), 0.f);
   }
   __syncthreads();
   const long long total_pix = (long long)N * H * W;
@@ -89,23 +95,25 @@ __global__ __launch_bounds__(256) void image_out_kernel(const T* __restrict__ x,
     const int iy = yy + tap / 3 - 1, ix = xx + tap % 3 - 1;
     if (iy < 0 || iy >= H || ix < 0 || ix >= W) continue;
     const T* src = x + (((long long)n * H + iy) * W + ix) * C0;
-    const float* wt = wl + tap * C0 * 3;
+    const float4* wt = wl + tap * C0;
     int c = 0;
     for (; c + 8 <= C0; c += 8) {   // 16- or 32-byte loads (rows start 16-byte aligned when C0 is a multiple of 8)
       float v[8];
       load8(src + c, v, (C0 & 7) == 0);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        acc[0] = fmaf(v[e], wt[(c + e) * 3], acc[0]);
-        acc[1] = fmaf(v[e], wt[(c + e) * 3 + 1], acc[1]);
-        acc[2] = fmaf(v[e], wt[(c + e) * 3 + 2], acc[2]);
+        const float4 ww = wt[c + e];   // the same address in every lane: one broadcast read for three products
+        acc[0] = fmaf(v[e], ww.x, acc[0]);
+        acc[1] = fmaf(v[e], ww.y, acc[1]);
+        acc[2] = fmaf(v[e], ww.z, acc[2]);
       }
     }
     for (; c < C0; ++c) {
       const float v = to_f32<T>(src[c]);
-      acc[0] = fmaf(v, wt[c * 3], acc[0]);
-      acc[1] = fmaf(v, wt[c * 3 + 1], acc[1]);
-      acc[2] = fmaf(v, wt[c * 3 + 2], acc[2]);
+      const float4 ww = wt[c];
+      acc[0] = fmaf(v, ww.x, acc[0]);
+      acc[1] = fmaf(v, ww.y, acc[1]);
+      acc[2] = fmaf(v, ww.z, acc[2]);
     }
   }
 #pragma unroll
@@ -133,7 +141,7 @@ template <typename T>
 void launch_image_out(const void* x, const void* w, const float* b, float* out_f32, uint8_t* out_u8, int N, int H, int W,
                       int C0, hipStream_t s) {
   const long long pix = (long long)N * H * W;
-  hipLaunchKernelGGL(image_out_kernel<T>, dim3((unsigned)((pix + 255) / 256)), dim3(256), (size_t)27 * C0 * sizeof(float),
+  hipLaunchKernelGGL(image_out_kernel<T>, dim3((unsigned)((pix + 255) / 256)), dim3(256), (size_t)9 * C0 * sizeof(float4),
                      s, (const T*)x, (const T*)w, b, out_f32, out_u8, N, H, W, C0);
 }
 template void launch_image_out<float>(const void*, const void*, const float*, float*, uint8_t*, int, int, int, int, hipStream_t);

@@ -163,13 +163,14 @@ def test_step_with_the_boundary_at_the_image(dtype, graph):
             want = I.to_u8(I.decode(P, want_lat[s]))
             mx, mean, same = _u8_gap(got[s], want)
             worst = (max(worst[0], mx), max(worst[1], mean), min(worst[2], same))
-            far = max(far, float((np.abs(got[s].astype(np.int32) - want.astype(np.int32)) > 8).mean()))
+            far = max(far, rel_l2(got[s], want))
     eng.close()
     print(f"{dtype} graph={graph}: u8 images, max level gap {worst[0]}, mean {worst[1]:.3f}, identical {worst[2]:.3f}, "
-          f"share of pixels more than 8 levels off {far:.4f}")
+          f"relative L2 of the u8 image {far:.3e}")
     if dtype == "fp32":
         assert worst[0] <= 1 and worst[2] >= 0.99
     else:
-        # bf16 through encoder, two U-Net evaluations per frame (the x0 prediction at t = 999 divides by 0.068) and
-        # decoder: judged by the mean gap and the share of far-off pixels; single pixels next to a ReLU kink can be far
-        assert worst[1] <= 2.0 and far <= 0.02
+        # bf16 through encoder, two U-Net evaluations per frame and decoder: the stated relative L2 bar, on the u8
+        # image (plus half a grey level of quantisation, 0.3e-2 at this image's rms); single pixels next to a ReLU
+        # kink can be far off, so the maximum is reported and not bounded
+        assert far <= TOL_BF16 + 0.3e-2 and worst[1] <= 2.0
