@@ -70,6 +70,12 @@ struct IgemmParams {
   float ln_eps;
   float* stats_out;        // [M][ceil(N/BN)][2] partial sums of this layer's bf16-rounded output rows, one part per column tile; null = none
   int no_splitk;           // layers with ln_stats or stats_out never split K (their epilogue must see whole sums)
+  // MFMA direct-to-LDS kernels only: a second K segment behind the taps, a 1x1 convolution over the channel concat of
+  // src3 | src4 (same pixels as the output: stride 1, no upsampling), K = ksize^2 (C1+C2) + C3 + C4.  All four
+  // channel counts multiples of 64.  Used to sum a ResBlock's 1x1 skip convolution into its second 3x3 convolution.
+  const void* src3;
+  const void* src4;
+  int C3, C4;
 };
 
 #define LN_MAX_PARTS 20   // most parts of row statistics a folded LayerNorm reads (column tiles of the producing layer)
@@ -180,8 +186,9 @@ void launch_ssf_reduce(const uint8_t* frame, const uint8_t* ref, uint8_t* spare,
 template <typename T>
 void launch_repack_rowmajor(const float* src, void* dst, int O, int I, int taps, int geglu_block, hipStream_t s);
 //  `in_scale` (may be null): per input channel factor applied before rounding (the scale of a folded LayerNorm)
+//  `ksteps_total` / `kstep0`: the matrix is one K segment of a wider packed matrix (0 / 0: it stands alone)
 void launch_repack_mfma(const float* src, void* dst, int O, int I, int taps, int geglu_block, const float* in_scale,
-                        hipStream_t s);
+                        int ksteps_total, int kstep0, hipStream_t s);
 // Vectors of a LayerNorm (gamma, beta over the I input channels) folded into the [O][I] matrix `src`, in the row order
 // of the packed matrix: wsum[n] = sum_i bf16(gamma_i w[n][i]) (what the matrix core multiplies), lnb[n] = sum_i beta_i w[n][i]
 void launch_ln_fold_vectors(const float* src, const float* gamma, const float* beta, float* wsum, float* lnb, int O, int I,

@@ -122,8 +122,10 @@ struct Entry {
   // derived vectors (row sums of the scaled weights, shift times weights) for this entry's rows
   bool ln_fold = false;
   size_t ln_g = 0, ln_b = 0, ln_wsum = 0, ln_lnb = 0;
+  // LA_MFMA only: the matrix is one K segment of a wider packed matrix (pk_total k-steps of 32 in all, this one from pk_off)
+  int pk_total = 0, pk_off = 0;
 };
-struct BiasFix { size_t lnb, bias; int n; };   // after loading: lnb[0..n) += bias[0..n)
+struct BiasFix { size_t lnb, bias; int n; bool copy = false; };   // after loading: lnb[0..n) += bias[0..n) (copy: =)
 
 struct LinW {
   size_t w = 0, b = 0;  // byte offsets into the weight arena (b: fp32)
@@ -448,7 +450,7 @@ struct Builder {
   struct ResW {
     float *g1, *b1, *g2, *b2;
     LinW c1, c2, skip, temb;
-    bool has_skip;
+    bool has_skip, fused_skip;
     size_t rowbias;  // persist offset, [max_batch][cout] fp32
   };
   ResW res_weights(const std::string& p, int c1in, int c2in, int cout) {
@@ -460,9 +462,37 @@ struct Builder {
     r.temb = f32w(p + ".temb", cout, temb_dim);
     r.g2 = fvec(p + ".norm2.g", cout, 2);
     r.b2 = fvec(p + ".norm2.b", cout, 3);
-    r.c2 = matw(p + ".conv2", cout, cout, 3, true, true, false, cout, 0);
     r.has_skip = cin != cout;
-    if (r.has_skip) r.skip = matw(p + ".skip", cout, cin, 1, true, true, false, c1in, c2in);
+    // With the direct-to-LDS matrix-core kernels the 1x1 skip convolution is summed into conv2 as a second K segment:
+    // one packed matrix [conv2 taps | skip], one bias vector (the sum of the two), one launch instead of two.
+    r.fused_skip = r.has_skip && mfma_ok(cout, 0, cout, false) && cout % 64 == 0 && c1in % 64 == 0 && c2in % 64 == 0;
+#ifdef SDSTREAM_DEVHOOKS
+    if (getenv("SDSTREAM_NO_SKIPFUSE")) r.fused_skip = false;
+#endif
+    if (r.fused_skip) {
+      const int k1 = 9 * cout, kt = k1 + cin;
+      LinW w;
+      w.N = cout; w.K = kt; w.mfma = true; w.has_bias = true;
+      w.w = walloc((size_t)cout * kt * e.elt);
+      add_entry(p + ".conv2.w", {cout, cout, 3, 3}, 0, LA_MFMA, w.w, cout, cout, 9, 0);
+      if (dry) { e.manifest.back().pk_total = kt / 32; e.manifest.back().pk_off = 0; }
+      const size_t b2 = walloc((size_t)cout * 4);
+      add_entry(p + ".conv2.b", {cout}, 1, LA_F32, b2, cout, 1, 1, 0);
+      add_entry(p + ".skip.w", {cout, cin, 1, 1}, 0, LA_MFMA, w.w, cout, cin, 1, 0);
+      if (dry) { e.manifest.back().pk_total = kt / 32; e.manifest.back().pk_off = k1 / 32; }
+      const size_t bs = walloc((size_t)cout * 4);
+      add_entry(p + ".skip.b", {cout}, 1, LA_F32, bs, cout, 1, 1, 0);
+      w.b = walloc((size_t)cout * 4);   // conv2.b + skip.b
+      if (dry) {
+        BiasFix f1{w.b, b2, cout, true}, f2{w.b, bs, cout, false};
+        e.bias_fixes.push_back(f1);
+        e.bias_fixes.push_back(f2);
+      }
+      r.c2 = w;
+    } else {
+      r.c2 = matw(p + ".conv2", cout, cout, 3, true, true, false, cout, 0);
+      if (r.has_skip) r.skip = matw(p + ".skip", cout, cin, 1, true, true, false, c1in, c2in);
+    }
     r.rowbias = palloc((size_t)e.max_batch * cout * 4);
     return r;
   }
@@ -498,11 +528,22 @@ struct Builder {
     afree(t2);
     const void* skip = x1;
     void* sk = nullptr;
-    if (r.has_skip) {
+    if (r.fused_skip) {
+      skip = nullptr;
+    } else if (r.has_skip) {
       sk = conv(x1, c1in, x2, c2in, H, W, H, W, 1, 1, 0, r.skip, nullptr, 0, nullptr, EPI_NONE);
       skip = sk;
     }
     void* out = conv(t3, cout, nullptr, 0, H, W, H, W, 3, 1, 0, r.c2, nullptr, 0, skip, EPI_NONE);
+    if (r.fused_skip) {   // second K segment: the block's input through the 1x1 weights
+      IgemmParams& g = e.ops.back().g;
+      g.src3 = x1; g.C3 = c1in;
+      g.src4 = x2; g.C4 = c2in;
+      g.K += c1in + c2in;
+      e.ops.back().flops_per_row += 2.0 * HW * (double)cout * (c1in + c2in);
+      e.ops.back().bytes_per_row += (double)HW * (c1in + c2in) * e.elt;
+      e.ops.back().bytes_fixed += (double)cout * (c1in + c2in) * e.elt;
+    }
     afree(t3);
     if (sk) afree(sk);
     return out;
@@ -1273,11 +1314,11 @@ int load_entries(sdstream* h, const std::vector<Entry>& entries, char* base, int
         break;
       case LA_MFMA:
         if (en.ln_fold) {
-          launch_repack_mfma(stage, dst, en.O, en.I, en.taps, en.geglu, (const float*)(base + en.ln_g), s);
+          launch_repack_mfma(stage, dst, en.O, en.I, en.taps, en.geglu, (const float*)(base + en.ln_g), 0, 0, s);
           launch_ln_fold_vectors(stage, (const float*)(base + en.ln_g), (const float*)(base + en.ln_b),
                                  (float*)(base + en.ln_wsum), (float*)(base + en.ln_lnb), en.O, en.I, en.geglu, s);
         } else {
-          launch_repack_mfma(stage, dst, en.O, en.I, en.taps, en.geglu, nullptr, s);
+          launch_repack_mfma(stage, dst, en.O, en.I, en.taps, en.geglu, nullptr, en.pk_total, en.pk_off, s);
         }
         break;
       case LA_BIAS_PERM: launch_permute_bias(stage, (float*)dst, en.O, en.geglu, s); break;
@@ -1287,8 +1328,10 @@ int load_entries(sdstream* h, const std::vector<Entry>& entries, char* base, int
   }
   hipFree(stage);
   if (rc) return rc;
-  for (const BiasFix& f : fixes)   // bias + shift-times-weights of a folded LayerNorm, once both are there
-    launch_add_f32((float*)(base + f.lnb), (const float*)(base + f.bias), f.n, s);
+  for (const BiasFix& f : fixes) {   // vectors made of two loaded ones (bias + shift-times-weights of a folded LayerNorm; two biases)
+    if (f.copy) launch_copy_rows_f32((const float*)(base + f.bias), (float*)(base + f.lnb), f.n, s);
+    else launch_add_f32((float*)(base + f.lnb), (const float*)(base + f.bias), f.n, s);
+  }
   HIP_TRY(h, hipDeviceSynchronize());
   return SDSTREAM_OK;
 }

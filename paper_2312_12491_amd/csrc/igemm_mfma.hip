@@ -541,13 +541,36 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, FastDi
               (unsigned)min(l_stage, stage_last) * 2048u;
   }
 
+  // The K axis may carry a second segment behind the ksize x ksize taps: a 1x1 convolution over src3 | src4 (the
+  // skip path of a ResBlock, summed into the same accumulators).  cur_* describe the segment the cursor is in.
   int l_c, l_ky, l_kx;
+  const char* cur_s1 = s1;
+  const char* cur_s2 = s2;
+  int cur_C1 = p.C1, cur_Ct = Ct, cur_ks = p.ksize, cur_off = 0;   // cur_off: added to the tap offsets (pad of segment 1)
+  bool seg2 = false;
+  auto enter_seg2 = [&]() {
+    seg2 = true;
+    cur_s1 = (const char*)p.src3;
+    cur_s2 = (const char*)p.src4;
+    cur_C1 = p.C3;
+    cur_Ct = p.C3 + p.C4;
+    cur_ks = 1;
+    cur_off = pad;
+    l_ky = 0;
+    l_kx = 0;
+  };
   {
     int kk = stage0 * 64;
-    int tap = fast_div(kk, p.fd_ct);
-    l_c = kk - tap * Ct;
-    l_ky = fast_div(tap, p.fd_ks);
-    l_kx = tap - l_ky * p.ksize;
+    const int k_seg1 = p.ksize * p.ksize * Ct;
+    if (p.C3 > 0 && kk >= k_seg1) {
+      enter_seg2();
+      l_c = kk - k_seg1;
+    } else {
+      int tap = fast_div(kk, p.fd_ct);
+      l_c = kk - tap * Ct;
+      l_ky = fast_div(tap, p.fd_ks);
+      l_kx = tap - l_ky * p.ksize;
+    }
   }
 
   // Per-lane source address and validity of every A load for the cursor's position.  Inside a tap and a source
@@ -557,13 +580,13 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, FastDi
   const char* aptr[NLA];   // meaningless (and unused) where !okv
   bool okv[NLA];
   auto set_tap = [&]() {
-    const bool live = l_ky < p.ksize;
+    const bool live = l_ky < cur_ks;
     const char* src;
     int Cs, c = l_c;
-    if (c < p.C1) { src = s1; Cs = p.C1; } else { src = s2; Cs = p.C2; c -= p.C1; }
+    if (c < cur_C1) { src = cur_s1; Cs = cur_C1; } else { src = cur_s2; Cs = cur_Ct - cur_C1; c -= cur_C1; }
 #pragma unroll
     for (int i = 0; i < NLA; ++i) {
-      const int iy = ld_y[i] + l_ky, ix = ld_x[i] + l_kx;
+      const int iy = ld_y[i] + l_ky + cur_off, ix = ld_x[i] + l_kx + cur_off;
       okv[i] = live && ld_ok[i] && (unsigned)iy < (unsigned)Hs && (unsigned)ix < (unsigned)Wsz;
       const unsigned lin = ld_pix0[i] + (unsigned)((iy >> ups) * p.Win + (ix >> ups));
       aptr[i] = src + (lin * (unsigned)Cs + (unsigned)c + ld_ch[i]) * 2u;
@@ -588,10 +611,11 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, FastDi
     }
     ++l_stage;
     l_c += 64;
-    if (l_c == p.C1 || l_c >= Ct) {       // next source of a concatenation, or next tap
-      if (l_c >= Ct) {
+    if (l_c == cur_C1 || l_c >= cur_Ct) {       // next source of a concatenation, next tap, or next segment
+      if (l_c >= cur_Ct) {
         l_c = 0;
-        if (++l_kx == p.ksize) { l_kx = 0; ++l_ky; }
+        if (++l_kx == cur_ks) { l_kx = 0; ++l_ky; }
+        if (l_ky == cur_ks && !seg2 && p.C3 > 0) enter_seg2();
       }
       set_tap();
     }
@@ -747,7 +771,7 @@ struct Choice { int variant, bn, splitk; };  // variant 0: 32-deep stages, weigh
 // than that split K if K is long, and otherwise fall back to 64-row tiles.
 Choice choose(const IgemmParams& p) {
   Choice c;
-  const bool k64 = p.C1 % 64 == 0 && p.C2 % 64 == 0;
+  const bool k64 = p.C1 % 64 == 0 && p.C2 % 64 == 0 && p.C3 % 64 == 0 && p.C4 % 64 == 0;
   const bool geglu = p.epilogue == EPI_GEGLU;
   const int bn0 = geglu ? 128 : p.N % 160 == 0 ? 160 : p.N % 128 == 0 ? 128 : 64;
   c.bn = bn0;
@@ -849,6 +873,7 @@ IgemmPlan igemm_mfma_plan(const IgemmParams& p) {
 
 bool igemm_mfma_supported(const IgemmParams& p) {
   if (p.C1 % 32 || p.C2 % 32 || p.N % 16) return false;
+  if (p.C3 > 0 && (p.C1 % 64 || p.C2 % 64 || p.C3 % 64 || p.C4 % 64 || p.upsample || p.stride != 1)) return false;
   if (p.epilogue == EPI_GEGLU && p.N % 128) return false;
   if (p.epilogue == EPI_SILU) return false;
   // the kernel addresses activations and weights with 32-bit byte offsets

@@ -313,7 +313,8 @@ __global__ void repack_rowmajor_kernel(const float* src, T* dst, int O, int I, i
 
 // MFMA B-fragment order for v_mfma_f32_16x16x32_bf16: dst[ntile][kstep][lane][8] with
 // column n = ntile*16 + lane%16 and k = kstep*32 + (lane/16)*8 + j, k = tap*I + i.
-__global__ void repack_mfma_kernel(const float* src, bf16_t* dst, int O, int I, int taps, int blk, const float* in_scale) {
+__global__ void repack_mfma_kernel(const float* src, bf16_t* dst, int O, int I, int taps, int blk, const float* in_scale,
+                                   int ksteps_total, int kstep0) {
   long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   long long K = (long long)I * taps;
   long long total = (long long)O * K;
@@ -330,7 +331,8 @@ __global__ void repack_mfma_kernel(const float* src, bf16_t* dst, int O, int I, 
   int so = geglu_src_row(n, O, blk);
   float w = src[((long long)so * I + i) * taps + tap];
   if (in_scale) w *= in_scale[i];
-  dst[idx] = (bf16_t)w;
+  const long long out = ksteps_total > 0 ? ((((long long)ntile * ksteps_total + kstep0 + kstep) * 64 + lane) << 3) + j : idx;
+  dst[out] = (bf16_t)w;
 }
 
 // one thread per packed row n; double accumulation (these vectors carry the whole mean term of the folded norm)
@@ -442,10 +444,10 @@ template void launch_repack_rowmajor<float>(const float*, void*, int, int, int, 
 template void launch_repack_rowmajor<bf16_t>(const float*, void*, int, int, int, int, hipStream_t);
 
 void launch_repack_mfma(const float* src, void* dst, int O, int I, int taps, int geglu_block, const float* in_scale,
-                        hipStream_t s) {
+                        int ksteps_total, int kstep0, hipStream_t s) {
   long long total = (long long)O * I * taps;
   hipLaunchKernelGGL(repack_mfma_kernel, dim3(blocks_for(total, 256, 1LL << 31)), dim3(256), 0, s, src, (bf16_t*)dst, O,
-                     I, taps, geglu_block, in_scale);
+                     I, taps, geglu_block, in_scale, ksteps_total, kstep0);
 }
 
 void launch_ln_fold_vectors(const float* src, const float* gamma, const float* beta, float* wsum, float* lnb, int O, int I,
