@@ -12,7 +12,10 @@ template <typename T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }
 
-enum { EPI_NONE = 0, EPI_GEGLU = 1, EPI_SILU = 2, EPI_RELU = 3 };   // RELU is applied after the residual sum
+enum { EPI_NONE = 0, EPI_GEGLU = 1, EPI_SILU = 2, EPI_RELU = 3, EPI_SOFTMAX = 4 };
+// RELU is applied after the residual sum.  SOFTMAX (MFMA kernels, 160-column tiles): the columns come in segments of
+// sm_lp (16 or 80) of which the first sm_len are real; the output is softmax in base 2 over each segment's real
+// columns (the weights carry log2(e)), zero elsewhere and in columns >= sm_cols.
 
 // Division by a launch-time constant through one multiply-high (the round-up method of Granlund and Montgomery):
 // exact for 0 <= x < 2^31.  An integer division by a run-time value costs ~30 instructions on this target, and
@@ -76,6 +79,8 @@ struct IgemmParams {
   const void* src3;
   const void* src4;
   int C3, C4;
+  int sm_lp, sm_len, sm_cols;   // EPI_SOFTMAX
+  int force_variant, force_bn;  // force_bn != 0: kernel variant (1: 128-row, 2: 64-row direct-to-LDS; 0: register-staged) and tile width to use, no split-K
 };
 
 #define LN_MAX_PARTS 20   // most parts of row statistics a folded LayerNorm reads (column tiles of the producing layer)
@@ -153,6 +158,13 @@ void launch_image_in(const uint8_t* img, const float* w, const float* b, void* o
 template <typename T>
 void launch_image_out(const void* x, const void* w, const float* b, float* out_f32, uint8_t* out_u8, int N, int H, int W,
                       int C0, hipStream_t s);
+
+// Per-prompt matrices of a folded cross-attention (bf16 path), see xattn.hip.  kv: the prompt's [L][2C] keys | values
+// (bf16, row pitch ld_kv elements); wq, wo: the site's q and output projections, fp32 row-major [C][C]; gamma, beta: the
+// LayerNorm in front of q; raw: fp32 scratch [Npad][C]; outputs: QK packed [Npad][C] with wsum / lnb [Npad], VO packed [C][Npad].
+void launch_xattn_fold(const void* kv, int ld_kv, const float* wq, const float* wo, const float* gamma, const float* beta,
+                       float* raw, void* qk_packed, float* wsum, float* lnb, void* vo_packed, int C, int heads, int d,
+                       int L, int Lp, int Npad, hipStream_t s);
 
 // e[row] = [cos(t f_j) ; sin(t f_j)], f_j = exp(-ln(1e4) j/half), evaluated in double.
 void launch_time_embedding(const int* t, float* out, int rows, int C0, hipStream_t s);

@@ -97,6 +97,8 @@ struct Op {
   double bytes_per_row;  // algorithmic bytes per sample (activations in + out)
   double bytes_fixed;    // weights
   int ln_src_op;         // >= 0: index of the op whose stats_out this op's folded LayerNorm reads
+  int xattn_site;        // >= 0: a GEMM of a folded cross-attention: its weights belong to the prompt slot of each row
+  int xattn_role;        //   1: rows x QK with softmax; 2: probabilities x VO
   // conv_in / conv_out (fp32 NCHW <-> NHWC activations) and image_in / image_out (u8 HWC image <-> NHWC activations)
   const float* cw_f32;
   const void* cw;
@@ -124,6 +126,8 @@ struct Entry {
   size_t ln_g = 0, ln_b = 0, ln_wsum = 0, ln_lnb = 0;
   // LA_MFMA only: the matrix is one K segment of a wider packed matrix (pk_total k-steps of 32 in all, this one from pk_off)
   int pk_total = 0, pk_off = 0;
+  bool raw_copy = false;   // also keep the fp32 tensor as it is, at raw_off
+  size_t raw_off = 0;
 };
 struct BiasFix { size_t lnb, bias; int n; bool copy = false; };   // after loading: lnb[0..n) += bias[0..n) (copy: =)
 
@@ -138,6 +142,12 @@ struct KVSite {
   LinW w;        // fused [2C][D]
   size_t cache;  // byte offset in the persistent arena: [2][L][2C] T
   int C;
+  // cross-attention folded into two GEMMs (bf16 matrix-core path): per prompt slot, in the persistent arena
+  bool xfold = false;
+  int heads = 0, d = 0, Lp = 0, Npad = 0;
+  size_t wq_raw = 0, wo_raw = 0, ln_g = 0, ln_b = 0;   // weight arena: fp32 copies of q / output projection, the norm in front of q
+  size_t qk = 0, vo = 0, wsum = 0, lnb = 0;            // persistent arena, slot 0; slot 1 follows at the *_stride
+  size_t mat_stride = 0, vec_stride = 0;
 };
 
 }  // namespace
@@ -170,6 +180,9 @@ struct sdstream {
   std::vector<KVSite> kv_sites;
   size_t off_emb = 0, off_h1 = 0, off_h2 = 0, off_tdev = 0, off_ctxT = 0;
   size_t off_sel_zero = 0, off_sel_step = 0;
+  size_t off_xraw = 0;     // fp32 scratch of the cross-attention fold
+  size_t xraw_floats = 0;
+  int neg_from = 0;        // rows from this index on use the negative prompt (set per U-Net call)
   size_t off_x[2] = {0, 0}, off_r[2] = {0, 0}, off_eps = 0, off_noise = 0, off_ab = 0;
   size_t off_unet_x = 0;  // fp32 input batch for unet_forward
   size_t off_zeros = 0;   // 256 bytes that stay zero
@@ -383,6 +396,7 @@ struct Builder {
     g.epilogue = epi;
     g.splitk = 1;
     op.ln_src_op = -1;
+    op.xattn_site = -1;
     int Nout = epi == EPI_GEGLU ? w.N / 2 : w.N;
     g.out = aalloc((size_t)Hout * Wout * Nout);
     op.rows_per_sample = Hout * Wout;
@@ -572,12 +586,39 @@ struct Builder {
     float* l2b = (float*)(e.weights + l2b_off);
     LinW q2 = fused({p + ".attn2.q"}, C, C);
     if (fold) v2 = fold_ln(1, C, 1, l2g_off, l2b_off);
+    // cross-attention folded into two GEMMs: prompt length padded to the softmax segment of the GEMM epilogue
+    const int Lp = L <= 16 ? 16 : (L > 64 && L <= 80 ? 80 : 0);
+    const int Npad = (heads * Lp + 63) / 64 * 64;
+    bool xfold = fold && Lp > 0 && heads * d == C && mfma_ok(C, 0, Npad, false) && mfma_ok(Npad, 0, C, false);
+#ifdef SDSTREAM_DEVHOOKS
+    if (getenv("SDSTREAM_NO_XFOLD")) xfold = false;
+#endif
+    size_t wq_raw = 0, wo_raw = 0;
+    if (xfold) {
+      wq_raw = walloc((size_t)C * C * 4);
+      if (dry) { e.manifest.back().raw_copy = true; e.manifest.back().raw_off = wq_raw; }
+    }
     KVSite site;
     site.w = fused({p + ".attn2.k", p + ".attn2.v"}, C, D);
     site.C = C;
     site.cache = palloc((size_t)2 * L * 2 * C * e.elt);
     e.kv_sites.push_back(site);
     LinW o2 = matw(p + ".attn2.o", C, C, 1, false, true, false, C, 0);
+    if (xfold) {
+      wo_raw = walloc((size_t)C * C * 4);
+      if (dry) { Entry& en = e.manifest[e.manifest.size() - 2]; en.raw_copy = true; en.raw_off = wo_raw; }   // (attn2.o.w, attn2.o.b)
+      KVSite& st = e.kv_sites.back();
+      st.xfold = true;
+      st.heads = heads; st.d = d; st.Lp = Lp; st.Npad = Npad;
+      st.wq_raw = wq_raw; st.wo_raw = wo_raw; st.ln_g = l2g_off; st.ln_b = l2b_off;
+      st.mat_stride = ((size_t)Npad * C * e.elt + 255) & ~(size_t)255;
+      st.vec_stride = ((size_t)Npad * 4 + 255) & ~(size_t)255;
+      st.qk = palloc(2 * st.mat_stride);
+      st.vo = palloc(2 * st.mat_stride);
+      st.wsum = palloc(2 * st.vec_stride);
+      st.lnb = palloc(2 * st.vec_stride);
+      if ((size_t)Npad * C > e.xraw_floats) e.xraw_floats = (size_t)Npad * C;
+    }
     const size_t l3g_off = fvec_off(p + ".ln3.g", C, 2), l3b_off = fvec_off(p + ".ln3.b", C, 3);
     float* l3g = (float*)(e.weights + l3g_off);
     float* l3b = (float*)(e.weights + l3b_off);
@@ -624,16 +665,57 @@ struct Builder {
       auto st2 = emit_stats();
       afree(a1);
       afree(h);
+      void* h3;
+      std::pair<void*, int> st3;
+      if (xfold) {
+        const KVSite& ks = e.kv_sites.back();
+        const int site_index = (int)e.kv_sites.size() - 1;
+        const double attn_flops = 4.0 * HW * (double)L * d * heads, lin_flops = 2.0 * HW * (double)C * C;
+        LinW wa;   // rows x QK^T, per-head softmax in the epilogue
+        wa.N = Npad; wa.K = C; wa.mfma = true;
+        void* pr = conv(h2, C, nullptr, 0, H, W, H, W, 1, 1, 0, wa, nullptr, 0, nullptr, EPI_SOFTMAX);
+        {
+          Op& op = e.ops.back();
+          op.g.W = e.persist + ks.qk;
+          op.g.ln_stats = (const float*)st2.first;
+          op.g.ln_wsum = (const float*)(e.persist + ks.wsum);
+          op.g.bias = (const float*)(e.persist + ks.lnb);
+          op.g.ln_eps = 1e-5f;
+          op.g.no_splitk = 1;
+          op.g.sm_lp = Lp; op.g.sm_len = L; op.g.sm_cols = heads * Lp;
+          op.ln_src_op = st2.second;
+          op.xattn_site = site_index;
+          op.xattn_role = 1;
+          op.flops_per_row = lin_flops + attn_flops / 2;   // algorithmic work of what it replaces: q projection, scores
+          op.bytes_fixed = (double)Npad * C * e.elt;
+        }
+        afree(st2.first);
+        LinW wb;   // probabilities x VO^T + bias + residual
+        wb.N = C; wb.K = Npad; wb.mfma = true; wb.has_bias = true; wb.b = o2.b;
+        h3 = conv(pr, Npad, nullptr, 0, H, W, H, W, 1, 1, 0, wb, nullptr, 0, h2, EPI_NONE);
+        {
+          Op& op = e.ops.back();
+          op.g.W = e.persist + ks.vo;
+          op.xattn_site = site_index;
+          op.xattn_role = 2;
+          op.flops_per_row = lin_flops + attn_flops / 2;   // output projection, probabilities x values
+          op.bytes_fixed = (double)Npad * C * e.elt;
+        }
+        st3 = emit_stats();
+        afree(pr);
+        afree(h2);
+      } else {
       void* qc = conv(h2, C, nullptr, 0, H, W, H, W, 1, 1, 0, q2, nullptr, 0, nullptr, EPI_NONE);
       read_stats(st2, v2);
       afree(st2.first);
       char* cache = e.persist + site.cache;
       void* a2 = attn(qc, C, cache, cache + (size_t)C * e.elt, 2 * C, HW, L, heads, d, true, (size_t)L * 2 * C);
       afree(qc);
-      void* h3 = conv(a2, C, nullptr, 0, H, W, H, W, 1, 1, 0, o2, nullptr, 0, h2, EPI_NONE);
-      auto st3 = emit_stats();
+      h3 = conv(a2, C, nullptr, 0, H, W, H, W, 1, 1, 0, o2, nullptr, 0, h2, EPI_NONE);
+      st3 = emit_stats();
       afree(a2);
       afree(h2);
+      }
       void* u = conv(h3, C, nullptr, 0, H, W, H, W, 1, 1, 0, ffi, nullptr, 0, nullptr, EPI_GEGLU);
       read_stats(st3, v3);
       afree(st3.first);
@@ -706,6 +788,7 @@ struct Builder {
     e.off_unet_x = palloc((size_t)e.max_batch * e.E * 4);
     e.off_splitk = palloc(kSplitKWorkspaceFloats * 4);
     e.off_zeros = palloc(256);
+    e.xraw_floats = 0;
     if (c.image_width > 0) {
       e.off_img_lat_in = palloc((size_t)c.n_streams * e.E * 4);
       e.off_img_lat_out = palloc((size_t)c.n_streams * e.E * 4);
@@ -839,6 +922,7 @@ struct Builder {
       e.ops.push_back(op);
     }
     afree(t);
+    e.off_xraw = palloc((e.xraw_floats ? e.xraw_floats : 64) * 4);
     e.flops_per_row = 0;
     for (const Op& op : e.ops) e.flops_per_row += op.flops_per_row;
   }
@@ -905,6 +989,7 @@ struct ImageBuilder {
     op.mfma = w.mfma;
     op.cls = w.mfma ? PC_IGEMM_MFMA : PC_IGEMM_VALU;
     op.ln_src_op = -1;
+    op.xattn_site = -1;
     IgemmParams& g = op.g;
     g.src1 = src; g.C1 = C; g.C2 = 0;
     g.Hin = Hin; g.Win = Win; g.Hout = Hout; g.Wout = Wout;
@@ -1120,6 +1205,36 @@ void launch_op(sdstream* h, const Op& op0, int N, const int* kv_select, int xfra
           const int bn = igemm_mfma_plan(pg).bn;
           g.ln_parts = (pg.N + bn - 1) / bn;
         }
+        if (op0.xattn_site >= 0) {
+          // The weights are per prompt: the rows of the positive prompt and those of the negative prompt (from row
+          // neg_from on) are two launches on row ranges, with the tile shape the whole range would get (the layer
+          // after this one reads one part of row statistics per column tile).
+          const KVSite& ks = h->kv_sites[op0.xattn_site];
+          const IgemmPlan plan = igemm_mfma_plan(g);
+          const int split = h->neg_from < N ? h->neg_from : N;
+          const int parts_out = (g.N + plan.bn - 1) / plan.bn;
+          for (int slot = 0; slot < 2; ++slot) {
+            const int r0 = slot == 0 ? 0 : split, r1 = slot == 0 ? split : N;
+            if (r1 <= r0) continue;
+            IgemmParams q = g;
+            const long long m0 = (long long)r0 * op0.rows_per_sample;
+            q.M = (r1 - r0) * op0.rows_per_sample;
+            q.force_variant = plan.variant;
+            q.force_bn = plan.bn;
+            q.src1 = (const char*)g.src1 + m0 * g.C1 * h->elt;
+            q.out = (char*)g.out + m0 * g.N * h->elt;
+            if (g.residual) q.residual = (const char*)g.residual + m0 * g.N * h->elt;
+            if (g.ln_stats) q.ln_stats = g.ln_stats + m0 * g.ln_parts * 2;
+            if (g.stats_out) q.stats_out = g.stats_out + m0 * parts_out * 2;
+            q.W = (const char*)g.W + (size_t)slot * ks.mat_stride;
+            if (op0.xattn_role == 1) {
+              q.ln_wsum = (const float*)((const char*)g.ln_wsum + (size_t)slot * ks.vec_stride);
+              q.bias = (const float*)((const char*)g.bias + (size_t)slot * ks.vec_stride);
+            }
+            launch_igemm_mfma(q, s);
+          }
+          break;
+        }
         launch_igemm_mfma(g, s);
       }
       else if (bf) launch_igemm_generic<bf16_t>(g, s);
@@ -1204,6 +1319,7 @@ int run_unet(sdstream* h, const float* x, float* eps, int N, const int* kv_selec
   // the first and last op read / write caller-visible buffers
   h->ops.front().cin = x;
   h->ops.back().cout_ = eps;
+  h->neg_from = for_step ? h->cfg.n_streams * nd : N;
   if (graph) {
     const int key = N * 2 + h->cur;  // the input batch alternates between two buffers
     auto it = h->graphs.find(key);
@@ -1281,6 +1397,14 @@ int build_kv(sdstream* h, const float* ctx, const float* neg, hipStream_t s) {
       if (site.w.mfma) launch_igemm_mfma(g, s);
       else if (bf) launch_igemm_generic<bf16_t>(g, s);
       else launch_igemm_generic<float>(g, s);
+      if (site.xfold)   // the per-prompt matrices of the folded cross-attention, from the keys / values just made
+        launch_xattn_fold(g.out, 2 * site.C, (const float*)(h->weights + site.wq_raw), (const float*)(h->weights + site.wo_raw),
+                          (const float*)(h->weights + site.ln_g), (const float*)(h->weights + site.ln_b),
+                          (float*)(h->persist + h->off_xraw), h->persist + site.qk + (size_t)slot * site.mat_stride,
+                          (float*)(h->persist + site.wsum + (size_t)slot * site.vec_stride),
+                          (float*)(h->persist + site.lnb + (size_t)slot * site.vec_stride),
+                          h->persist + site.vo + (size_t)slot * site.mat_stride, site.C, site.heads, site.d, c.context_len,
+                          site.Lp, site.Npad, s);
     }
   }
   HIP_TRY(h, hipGetLastError());
@@ -1306,6 +1430,7 @@ int load_entries(sdstream* h, const std::vector<Entry>& entries, char* base, int
     if (er != hipSuccess) { rc = fail(h, SDSTREAM_E_HIP, "hipMemcpy: %s", hipGetErrorString(er)); break; }
     src += en.count;
     void* dst = base + en.dst_off;
+    if (en.raw_copy) launch_copy_rows_f32(stage, (float*)(base + en.raw_off), (long long)en.count, s);
     switch (en.action) {
       case LA_F32: launch_copy_rows_f32(stage, (float*)dst, (long long)en.count, s); break;
       case LA_ROWMAJOR:
@@ -1699,6 +1824,7 @@ int sdstream_step_image(sdstream_t* h, const uint8_t* frame, const float* contex
   h->ops.back().cout_ = (float*)(h->persist + h->off_eps);
   const int* sel = (const int*)(h->persist + h->off_sel_step);
   const int xframe_rows = (h->cfg.cfg_mode == SDSTREAM_CFG_FULL ? 2 : 1) * S * n;
+  h->neg_from = S * n;
   auto launch_all = [&](hipStream_t st) {   // image -> latent -> one Stream Batch step -> latent -> image
     for (const Op& op : h->img_enc_ops) launch_op(h, op, S, nullptr, 0, st);
     launch_stream_head(p, st);

@@ -46,6 +46,12 @@ template <int I> struct IC { static constexpr int value = I; };
 // sum over the four lanes {l, l^16, l^32, l^48} (the lanes that hold one output row), on the vector ALU:
 // v_permlane16_swap / v_permlane32_swap with both operands equal leave (x[l], x[l^16]) resp. (x[l], x[l^32]) in a lane
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float quad_max(float x) {
+  u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
 __device__ __forceinline__ float quad_sum(float x) {
   u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
@@ -201,6 +207,60 @@ __device__ __forceinline__ void epilogue_store(const IgemmParams& p, f32x4 (&acc
         const int oc = ((gnt0 + nt) >> 1) * 16 + ncol;
         *(bf16x4*)(out + (long long)m * Nout + oc) = o;
       }
+    }
+    return;
+  }
+  if (p.epilogue == EPI_SOFTMAX) {
+    // A wave's 16*NT columns are whole segments of SEG n-tiles (NT n-tiles = one 80-column head, or 16-column heads):
+    // a row's segment lives in the four lanes that share the row, 4*SEG values each.
+    auto softmax_rows = [&](auto segc) {
+      constexpr int SEG = decltype(segc)::value;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const int m = mbase + mt * 16 + (lane & 15);
+#pragma unroll
+        for (int s0 = 0; s0 + SEG <= NT; s0 += SEG) {
+          float e[SEG][4];
+          bool ok[SEG][4];
+          float mx = -3.0e38f;
+#pragma unroll
+          for (int t = 0; t < SEG; ++t) {
+            const f32x4 x = acc[mt][s0 + t] + addv[s0 + t];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+              const int col = (gnt0 + s0 + t) * 16 + ncol + v;
+              ok[t][v] = t * 16 + ncol + v < p.sm_len && col < p.sm_cols;
+              e[t][v] = x[v];
+              if (ok[t][v]) mx = fmaxf(mx, x[v]);
+            }
+          }
+          mx = quad_max(mx);
+          float sum = 0.f;
+#pragma unroll
+          for (int t = 0; t < SEG; ++t)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+              e[t][v] = ok[t][v] ? __builtin_amdgcn_exp2f(e[t][v] - mx) : 0.f;
+              sum += e[t][v];
+            }
+          sum = quad_sum(sum);
+          const float inv = sum > 0.f ? 1.0f / sum : 0.f;
+          if (m < p.M) {
+#pragma unroll
+            for (int t = 0; t < SEG; ++t) {
+              const int n = (gnt0 + s0 + t) * 16 + ncol;
+              if (n >= p.N) continue;
+              bf16x4 o;
+#pragma unroll
+              for (int v = 0; v < 4; ++v) o[v] = (bf16_t)(e[t][v] * inv);
+              *(bf16x4*)(out + (long long)m * Nout + n) = o;
+            }
+          }
+        }
+      }
+    };
+    if constexpr (NT == 5) {
+      if (p.sm_lp == 80) softmax_rows(IC<5>{}); else softmax_rows(IC<1>{});
     }
     return;
   }
@@ -773,7 +833,8 @@ Choice choose(const IgemmParams& p) {
   Choice c;
   const bool k64 = p.C1 % 64 == 0 && p.C2 % 64 == 0 && p.C3 % 64 == 0 && p.C4 % 64 == 0;
   const bool geglu = p.epilogue == EPI_GEGLU;
-  const int bn0 = geglu ? 128 : p.N % 160 == 0 ? 160 : p.N % 128 == 0 ? 128 : 64;
+  const bool softmax = p.epilogue == EPI_SOFTMAX;   // its segments need the 80-column wave tile
+  const int bn0 = softmax ? 160 : geglu ? 128 : p.N % 160 == 0 ? 160 : p.N % 128 == 0 ? 128 : 64;
   c.bn = bn0;
   c.splitk = 1;
   if (!k64) {
@@ -825,6 +886,12 @@ Choice choose(const IgemmParams& p) {
   }
   // a layer that leaves row statistics writes one part per column tile, and the reader takes at most LN_MAX_PARTS
   if (p.stats_out && (p.N + c.bn - 1) / c.bn > LN_MAX_PARTS) c.bn = 160;
+  if (softmax) c.bn = 160;
+  if (p.force_bn) {   // a launch on a sub-range of rows keeps the tile shape chosen for the whole range
+    c.variant = p.force_variant;
+    c.bn = p.force_bn;
+    sk = 1;
+  }
   if (!may_split) sk = 1;
   if ((long long)sk * mn > p.workspace_floats) sk = (int)(p.workspace_floats / mn);
   c.splitk = sk > 1 ? sk : 1;
