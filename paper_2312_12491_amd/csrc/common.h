@@ -80,6 +80,7 @@ struct IgemmParams {
   const void* src4;
   int C3, C4;
   int sm_lp, sm_len, sm_cols;   // EPI_SOFTMAX
+  int dev_exp;                  // development builds only: bit mask of timing experiments (results are wrong with any bit set)
   int force_variant, force_bn;  // force_bn != 0: kernel variant (1: 128-row, 2: 64-row direct-to-LDS; 0: register-staged) and tile width to use, no split-K
 };
 

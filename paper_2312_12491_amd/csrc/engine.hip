@@ -1992,9 +1992,13 @@ static int prof_drain(sdstream* h) {
     if (r.op >= 0 && print_ops) {
       const Op& op = h->ops[r.op];
       if (op.kind == OP_IGEMM)
-        fprintf(stderr, "op %3d %-11s M=%d N=%d K=%d ks=%d st=%d up=%d epi=%d res=%d  %.1f us  %.1f TF/s\n", r.op,
+      {
+        IgemmPlan pl{0, 0, 0, 0};
+        if (op.mfma) pl = igemm_mfma_plan(mfma_params(h, op, r.N));
+        fprintf(stderr, "op %3d %-11s M=%d N=%d K=%d ks=%d st=%d up=%d epi=%d res=%d v=%d bn=%d sk=%d  %.1f us  %.1f TF/s\n", r.op,
                 kProfNames[r.cls], r.N * op.rows_per_sample, op.g.N, op.g.K, op.g.ksize, op.g.stride, op.g.upsample,
-                op.g.epilogue, op.g.residual ? 1 : 0, ms * 1e3, r.flops / (ms * 1e-3) / 1e12);
+                op.g.epilogue, op.g.residual ? 1 : 0, pl.variant, pl.bn, pl.splitk, ms * 1e3, r.flops / (ms * 1e-3) / 1e12);
+      }
       else if (op.kind == OP_ATTN)
         fprintf(stderr, "op %3d %-11s Sq=%d Skv=%d heads=%d d=%d  %.1f us  %.1f TF/s\n", r.op, kProfNames[r.cls],
                 op.at.Sq, op.at.Skv, op.at.heads, op.at.d, ms * 1e3, r.flops / (ms * 1e-3) / 1e12);

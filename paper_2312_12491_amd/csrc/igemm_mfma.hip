@@ -67,6 +67,9 @@ __device__ __forceinline__ float quad_sum(float x) {
 __device__ __forceinline__ void ln_rows_to_lds(const IgemmParams& p, int m0, int BM, float* lnrow) {
   const int r = threadIdx.x;
   if (p.ln_stats == nullptr || r >= BM) return;
+#ifdef SDSTREAM_DEVHOOKS
+  if (p.dev_exp & 8) { lnrow[r * 2] = 0.f; lnrow[r * 2 + 1] = 1.f; return; }
+#endif
   const int m = min(m0 + r, p.M - 1);
   const float2* src = (const float2*)p.ln_stats + (long long)m * p.ln_parts;
   // all parts requested at once (one memory round trip instead of one per part); surplus slots re-read the last part
@@ -205,6 +208,13 @@ __device__ __forceinline__ void epilogue_store(const IgemmParams& p, f32x4 (&acc
 #pragma unroll
         for (int v = 0; v < 4; ++v) o[v] = (bf16_t)(a[v] * gelu_erf(g[v]));
         const int oc = ((gnt0 + nt) >> 1) * 16 + ncol;
+#ifdef SDSTREAM_DEVHOOKS
+        if (p.dev_exp & 1) {
+#pragma unroll
+          for (int v = 0; v < 4; ++v) o[v] = (bf16_t)(a[v] * g[v]);
+        }
+        if ((p.dev_exp & 2) && a[0] != 12345.678f) continue;
+#endif
         *(bf16x4*)(out + (long long)m * Nout + oc) = o;
       }
     }
@@ -719,6 +729,9 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, FastDi
     for (int nt = 0; nt < NT; ++nt) bfr[ks][nt] = *(const bf16x8*)(sb + ((wn * NT + nt) * 2 + ks) * 1024 + lane * 16);
   };
   auto mfmas = [&](int ks) {
+#ifdef SDSTREAM_DEVHOOKS
+    if (p.dev_exp & 4) return;
+#endif
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -954,6 +967,10 @@ bool igemm_mfma_supported(const IgemmParams& p) {
 
 void launch_igemm_mfma(const IgemmParams& p0, hipStream_t s) {
   IgemmParams p = p0;
+#ifdef SDSTREAM_DEVHOOKS
+  static const int dev_exp = getenv("SDSTREAM_EXP") ? atoi(getenv("SDSTREAM_EXP")) : 0;
+  p.dev_exp = dev_exp;
+#endif
   const IgemmPlan c = igemm_mfma_plan(p);
   p.splitk = c.splitk;
   p.xcd_chunked = (long long)p.N * p.K > (long long)p.M * (p.C1 + p.C2) ? 1 : 0;
