@@ -80,6 +80,10 @@ struct IgemmParams {
   const void* src4;
   int C3, C4;
   int sm_lp, sm_len, sm_cols;   // EPI_SOFTMAX
+  // MFMA kernels: rows from slot_m on (a multiple of the row tile) use a second set of weights / vectors, slot_w_bytes
+  // behind W and slot_v_bytes behind bias and ln_wsum (the negative prompt's matrices of a folded cross-attention)
+  int slot_m;
+  long long slot_w_bytes, slot_v_bytes;
   int dev_exp;                  // development builds only: bit mask of timing experiments (results are wrong with any bit set)
   int force_variant, force_bn;  // force_bn != 0: kernel variant (1: 128-row, 2: 64-row direct-to-LDS; 0: register-staged) and tile width to use, no split-K
 };

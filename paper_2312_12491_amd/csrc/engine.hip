@@ -1213,6 +1213,14 @@ void launch_op(sdstream* h, const Op& op0, int N, const int* kv_select, int xfra
           const IgemmPlan plan = igemm_mfma_plan(g);
           const int split = h->neg_from < N ? h->neg_from : N;
           const int parts_out = (g.N + plan.bn - 1) / plan.bn;
+          const long long split_m = (long long)split * op0.rows_per_sample;
+          if (split > 0 && split < N && split_m % plan.bm == 0) {   // no row tile straddles the two prompts: one launch
+            g.slot_m = (int)split_m;
+            g.slot_w_bytes = (long long)ks.mat_stride;
+            g.slot_v_bytes = op0.xattn_role == 1 ? (long long)ks.vec_stride : 0;
+            launch_igemm_mfma(g, s);
+            break;
+          }
           for (int slot = 0; slot < 2; ++slot) {
             const int r0 = slot == 0 ? 0 : split, r1 = slot == 0 ? split : N;
             if (r1 <= r0) continue;

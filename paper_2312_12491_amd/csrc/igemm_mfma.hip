@@ -139,11 +139,12 @@ __device__ __forceinline__ void epilogue_load(const IgemmParams& p, EpilogueIn<M
   for (int nt = 0; nt < NT; ++nt) {
     const int n = min((gnt0 + nt) * 16 + ncol, p.N - 4);   // clamped: columns past N are never stored
     // absent terms are read from the zero page: a select on the loaded value would be a use
-    const float* bsrc = p.bias ? p.bias + n : (const float*)p.zeros;
+    const long long voff = (p.slot_m > 0 && mbase >= p.slot_m) ? p.slot_v_bytes / 4 : 0;   // wave-uniform
+    const float* bsrc = p.bias ? p.bias + voff + n : (const float*)p.zeros;
     const float* rsrc = in.one_sample ? p.rowbias + (long long)sample0 * p.rowbias_ld + n : (const float*)p.zeros;
     in.biasv[nt] = *(const f32x4*)bsrc;
     in.rbv[nt] = *(const f32x4*)rsrc;
-    in.wsv[nt] = *(const f32x4*)(p.ln_wsum ? p.ln_wsum + n : (const float*)p.zeros);
+    in.wsv[nt] = *(const f32x4*)(p.ln_wsum ? p.ln_wsum + voff + n : (const float*)p.zeros);
   }
   if (res && p.epilogue != EPI_GEGLU) {   // (plain and ReLU epilogues)
 #pragma unroll
@@ -365,7 +366,7 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma_kernel(IgemmParams p, FastD
   const int ups = p.upsample;
   const char* s1 = (const char*)p.src1;
   const char* s2 = (const char*)p.src2;
-  const char* Wp = (const char*)p.W;
+  const char* Wp = (const char*)p.W + ((p.slot_m > 0 && m0 >= p.slot_m) ? p.slot_w_bytes : 0);
 
   // ---- loader slots of this thread: output pixel of the row, top-left tap position, LDS address
   int ld_y[NLD], ld_x[NLD], ld_lds[NLD];
@@ -569,7 +570,7 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, FastDi
   const int ups = p.upsample;
   const char* s1 = (const char*)p.src1;
   const char* s2 = (const char*)p.src2;
-  const char* Wp = (const char*)p.W;
+  const char* Wp = (const char*)p.W + ((p.slot_m > 0 && m0 >= p.slot_m) ? p.slot_w_bytes : 0);
   const char* zeros = (const char*)p.zeros;
   const unsigned lds0 = (unsigned)(unsigned long long)(__attribute__((address_space(3))) void*)lds;
   float* lnrow = (float*)(lds + NBUF * STAGE);   // [BM][2] mean, rstd of the input rows (folded LayerNorm)
