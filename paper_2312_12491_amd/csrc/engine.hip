@@ -2063,7 +2063,10 @@ int sdstream_mfma_ceiling(sdstream_t* h, int32_t iters, double* tflops_out, void
   int dev = 0, cus = 0;
   HIP_TRY(h, hipGetDevice(&dev));
   HIP_TRY(h, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-  const int blocks = cus * 2;   // two 4-wave blocks per compute unit: two waves per SIMD
+  int blocks = cus * 2;   // two 4-wave blocks per compute unit: two waves per SIMD
+#ifdef SDSTREAM_DEVHOOKS
+  if (const char* e = getenv("SDSTREAM_CEIL_BPC")) blocks = cus * atoi(e);
+#endif
   float* sink = (float*)h->persist;   // only ever compared against, never written or read
   hipEvent_t e0, e1;
   HIP_TRY(h, hipEventCreate(&e0));

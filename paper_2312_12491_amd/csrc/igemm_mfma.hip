@@ -509,13 +509,17 @@ __global__ __launch_bounds__(256, 2) void igemm_mfma_kernel(IgemmParams p, FastD
 // fetches the row's 16-byte chunk j ^ ((r >> 1) & 7) and the fragment reads apply the same XOR, which spreads
 // the 16 rows of a fragment over all banks.  Rows outside the image or past M read the zero page instead.
 //
-// Pipeline (NBUF LDS buffers, loads NBUF stages ahead): a wave reads ALL fragments of stage s into registers,
-// the block synchronises, and the buffer is immediately refilled with stage s+NBUF while the MFMAs of stage s
-// run; stages s+1 .. s+NBUF-1 are already in flight in the other buffers.  NBUF = 2 is what is built: deeper rings
-// (3 buffers with 128-row tiles, 3 to 6 with 64-row tiles) were slower on every layer of the SD-shaped net, because the
-// larger LDS footprint leaves a compute unit with fewer resident blocks; so were 256-row tiles on 8 waves (one block
-// per compute unit, weight columns fetched once for twice the rows: 121 us against 105 us on the 16384x640x5760
-// layer - the eight waves move in step, where two independent blocks overlap their load and MFMA phases).  The loads are issued from inline assembly and
+// Pipeline, three shapes (launch_ring picks one per launch):
+//  * NBUF = 2, two barriers per stage: a wave reads ALL fragments of stage s into registers, the block synchronises,
+//    and the buffer is immediately refilled with stage s+2 while the MFMAs of stage s run.  For launches with two
+//    blocks per compute unit (three buffers would leave room for one).
+//  * NBUF = 3, ONEBAR: loads run two stages ahead into the buffer whose stage was multiplied before the last
+//    barrier, so the barrier that publishes stage s also frees the buffer of stage s-1: one barrier per stage.
+//    -10 % on the launches with one block per unit; a fourth buffer (three stages ahead) gains nothing more.
+//  * KG = 2: eight waves, two groups with two buffers each; group g multiplies stages g, g+2, ... of the block's
+//    range and the groups swap halves of their accumulators through LDS before the epilogue.
+// 256-row tiles on 8 waves (weight columns fetched once for twice the rows) were slower: 121 us against 105 us on
+// the 16384x640x5760 layer.  The loads are issued from inline assembly and
 // waited for with explicit vmcnt values (every wave issues the same number per stage), because the compiler
 // would otherwise drain all outstanding loads before each LDS read.
 // ---------------------------------------------------------------------------------------------------
@@ -546,9 +550,11 @@ template <int NBUF, int NLOADS> __device__ __forceinline__ void wait_stages_ahea
   }
 }
 
-template <int BM, int BN, int NBUF>
-__global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, FastDiv mtiles, FastDiv ntiles, int ksteps_total,
-                                                           int stages_per_split) {
+template <int BM, int BN, int NBUF, bool ONEBAR, int KG>
+__global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void igemm_dma_kernel(IgemmParams p, FastDiv mtiles,
+                                                                             FastDiv ntiles, int ksteps_total,
+                                                                             int stages_per_split) {
+  static_assert(KG == 1 || (KG == 2 && NBUF == 2 && !ONEBAR && BM == 128), "two wave groups: two buffers each, 128 rows");
   constexpr int WM = 2, WN = 2, NW = 4;
   constexpr int WTM = BM / WM, WTN = BN / WN, MT = WTM / 16, NT = WTN / 16;
   constexpr int NLA = BM / 8 / NW, NLB = BN / 8 / NW;   // 1 KB loads per wave and stage: activation row groups, weight fragments
@@ -558,7 +564,8 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, FastDi
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // NBUF stages of [A | B]
 
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6) & 3;   // within its group
+  const int grp = KG == 1 ? 0 : __builtin_amdgcn_readfirstlane(tid >> 8);
   const int wm = wave & 1, wn = wave >> 1;
   const TileId tile = tile_of_block(mtiles, ntiles, p.splitk > 1 ? p.splitk : 1, p.xcd_chunked);
   if (!tile.valid) return;  // padding block (uniform for the whole block, before any barrier)
@@ -572,8 +579,9 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, FastDi
   const char* s2 = (const char*)p.src2;
   const char* Wp = (const char*)p.W + ((p.slot_m > 0 && m0 >= p.slot_m) ? p.slot_w_bytes : 0);
   const char* zeros = (const char*)p.zeros;
-  const unsigned lds0 = (unsigned)(unsigned long long)(__attribute__((address_space(3))) void*)lds;
-  float* lnrow = (float*)(lds + NBUF * STAGE);   // [BM][2] mean, rstd of the input rows (folded LayerNorm)
+  unsigned char* ring = lds + grp * (NBUF * STAGE);   // this group's stage buffers
+  const unsigned lds0 = (unsigned)(unsigned long long)(__attribute__((address_space(3))) void*)ring;
+  float* lnrow = (float*)(lds + KG * NBUF * STAGE);   // [BM][2] mean, rstd of the input rows (folded LayerNorm)
   float* red = lnrow + BM * 2;                   // [BM][2] row statistics of the other column half
 
   // A loads of this lane: load i of wave w fills LDS rows (i*NW + w)*8 .. +7
@@ -600,7 +608,9 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, FastDi
   const int stage0 = tile.split * stages_per_split;
   int nstages = total_stages - stage0;
   if (nstages > stages_per_split) nstages = stages_per_split;
-  int l_stage = stage0;
+  const int nstages_all = nstages;
+  if constexpr (KG > 1) nstages = (nstages - grp + KG - 1) / KG;   // group g takes stages g, g + KG, ... of the block's range
+  int l_stage = stage0 + grp;
   const int stage_last = total_stages - 1;
   const char* bptr[NLB];   // this lane's 16 bytes of fragment i in the cursor's stage
 #pragma unroll
@@ -631,7 +641,7 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, FastDi
     l_kx = 0;
   };
   {
-    int kk = stage0 * 64;
+    int kk = (stage0 + grp) * 64;
     const int k_seg1 = p.ksize * p.ksize * Ct;
     if (p.C3 > 0 && kk >= k_seg1) {
       enter_seg2();
@@ -666,20 +676,12 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, FastDi
   set_tap();
 
   // issues the NLOADS loads of the cursor's stage into LDS buffer `buf` and advances the cursor
-  auto issue = [&](int buf) {
-    const unsigned sa = lds0 + buf * STAGE;
+  auto advance = [&]() {
 #pragma unroll
-    for (int i = 0; i < NLA; ++i) {
-      const char* g = okv[i] ? aptr[i] : zeros;
-      lds_dma16(g, sa + (i * NW + wave) * 1024);
-      aptr[i] += 128;
-    }
+    for (int i = 0; i < NLA; ++i) aptr[i] += 128;
     const int bstep = l_stage < stage_last ? 2048 : 0;   // the pointer never leaves the packed weights
 #pragma unroll
-    for (int i = 0; i < NLB; ++i) {
-      lds_dma16(bptr[i], sa + ABYTES + (i * NW + wave) * 1024);
-      bptr[i] += bstep;
-    }
+    for (int i = 0; i < NLB; ++i) bptr[i] += bstep;
     ++l_stage;
     l_c += 64;
     if (l_c == cur_C1 || l_c >= cur_Ct) {       // next source of a concatenation, next tap, or next segment
@@ -690,6 +692,18 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, FastDi
       }
       set_tap();
     }
+  };
+  auto issue = [&](int buf) {
+    const unsigned sa = lds0 + buf * STAGE;
+#pragma unroll
+    for (int i = 0; i < NLA; ++i) {
+      const char* g = okv[i] ? aptr[i] : zeros;
+      lds_dma16(g, sa + (i * NW + wave) * 1024);
+    }
+#pragma unroll
+    for (int i = 0; i < NLB; ++i) lds_dma16(bptr[i], sa + ABYTES + (i * NW + wave) * 1024);
+#pragma unroll
+    for (int g = 0; g < KG; ++g) advance();
   };
 
   f32x4 acc[MT][NT];
@@ -711,8 +725,9 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, FastDi
   // loads are older than every LDS load below, so the first stage's vmcnt wait covers them.
   EpilogueIn<MT, NT> epi_in;
   if constexpr (BM == 64) epilogue_load<MT, NT>(p, epi_in, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo);
+  constexpr int PRE = ONEBAR ? NBUF - 1 : NBUF;   // stages in flight ahead of the one being multiplied
 #pragma unroll
-  for (int b = 0; b < NBUF; ++b)
+  for (int b = 0; b < PRE; ++b)
     if (b < nstages) issue(b);
   // after the first stages are on their way: the wait for these loads also waits for those, which the loop would do next anyway
   ln_rows_to_lds(p, m0, BM, lnrow);
@@ -721,7 +736,7 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, FastDi
   // stage's first k-step, so half of the LDS read latency sits in the shadow of the matrix cores.
   bf16x8 af[2][MT], bfr[2][NT];
   auto read_frags = [&](int ks, int buf) {
-    const unsigned char* sa = lds + buf * STAGE;
+    const unsigned char* sa = ring + buf * STAGE;
     const unsigned char* sb = sa + ABYTES;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -740,11 +755,44 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, FastDi
         acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[ks][nt], af[ks][mt], acc[mt][nt], 0, 0, 0);
   };
   static_assert((NBUF - 1) * NLOADS < 64, "vmcnt is a 6-bit counter");
+  static_assert(!ONEBAR || NBUF >= 3, "one barrier per stage needs a buffer nobody reads");
   int buf = 0;
+  if constexpr (KG == 2) {
+    // Two wave groups split the block's K range stage by stage (in-block split-K: a compute unit with one block
+    // still has two waves per SIMD, and no partial tile leaves the unit).  Both run the two-barrier loop, the
+    // second group half an iteration behind: while one group reads fragments the other issues its loads, and
+    // every barrier is passed by all eight waves (each group uses every other one).
+    const int iters = (nstages_all + 1) >> 1;   // of the first group; the second has as many or one less
+    if (grp == 1) __syncthreads();
+    for (int s = 0; s < iters; ++s) {
+      const bool live = s < nstages;
+      if (live) wait_stages_ahead<NBUF, NLOADS>(nstages - 1 - s);
+      __syncthreads();
+      if (live) {
+        read_frags(0, buf);
+        if (s > 0) {
+          mfmas(1);
+#pragma unroll
+          for (int i = 0; i < MT + NT; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+          }
+        }
+        read_frags(1, buf);
+      }
+      __syncthreads();
+      if (live) {
+        if (s + NBUF < nstages) issue(buf);
+        mfmas(0);
+        buf ^= 1;
+      }
+    }
+    if (grp == 0) __syncthreads();
+  } else {
   for (int s = 0; s < nstages; ++s) {
     // all but this wave's loads of the stages after s (NBUF-1 of them, fewer at the end: nothing is loaded past
     // the last stage - on the short-K layers two more stages would be a third of the traffic) have landed
-    wait_stages_ahead<NBUF, NLOADS>(nstages - 1 - s);
+    wait_stages_ahead<PRE, NLOADS>(nstages - 1 - s);
     __syncthreads();                     // ... and everyone else's part of stage s too
     read_frags(0, buf);
     if (s > 0) {
@@ -756,15 +804,60 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(IgemmParams p, FastDi
       }
     }
     read_frags(1, buf);
-    __syncthreads();                     // every wave holds its fragments: the buffer can be refilled
-    if (s + NBUF < nstages) issue(buf);  // stage s+NBUF
+    if constexpr (ONEBAR) {
+      // every wave has passed this stage's barrier, so it holds its fragments of stage s-1: that buffer is free
+      if (s + PRE < nstages) issue(buf == 0 ? NBUF - 1 : buf - 1);   // stage s+NBUF-1
+    } else {
+      __syncthreads();                     // every wave holds its fragments: the buffer can be refilled
+      if (s + NBUF < nstages) issue(buf);  // stage s+NBUF
+    }
     mfmas(0);
     buf = buf + 1 == NBUF ? 0 : buf + 1;
   }
+  }
   if (nstages > 0) mfmas(1);
-  if constexpr (BM != 64) epilogue_load<MT, NT>(p, epi_in, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo);
-  epilogue_store<MT, NT>(p, acc, epi_in, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo, tile.split,
-                         lnrow + wm * WTM * 2, red + wm * WTM * 2, wn, tile.ntile, (int)ntiles.d);
+  if constexpr (KG == 2) {
+    // The groups swap halves of their accumulators through LDS: each ends up with the sums of 32 of the wave
+    // tile's 64 rows and runs the epilogue on those.
+    constexpr int MH = MT / 2;
+    const int row0 = wm * WTM + grp * (MH * 16);
+    EpilogueIn<MH, NT> hin;
+    epilogue_load<MH, NT>(p, hin, m0 + row0, (n0 + wn * WTN) >> 4, lane, HWo);
+    f32x4 fin[MH][NT];
+    f32x4* xch = (f32x4*)lds;   // [group][wave][MH * NT][lane]
+    __syncthreads();            // both groups are done with the stage buffers
+    f32x4* mine = xch + ((grp * NW + wave) * (MH * NT)) * 64 + lane;
+    const f32x4* theirs = xch + (((grp ^ 1) * NW + wave) * (MH * NT)) * 64 + lane;
+    if (grp == 0) {
+#pragma unroll
+      for (int i = 0; i < MH; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) mine[(i * NT + j) * 64] = acc[MH + i][j];
+    } else {
+#pragma unroll
+      for (int i = 0; i < MH; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) mine[(i * NT + j) * 64] = acc[i][j];
+    }
+    __syncthreads();
+    if (grp == 0) {
+#pragma unroll
+      for (int i = 0; i < MH; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) fin[i][j] = acc[i][j] + theirs[(i * NT + j) * 64];
+    } else {
+#pragma unroll
+      for (int i = 0; i < MH; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) fin[i][j] = theirs[(i * NT + j) * 64] + acc[MH + i][j];
+    }
+    epilogue_store<MH, NT>(p, fin, hin, m0 + row0, (n0 + wn * WTN) >> 4, lane, HWo, tile.split, lnrow + row0 * 2,
+                           red + row0 * 2, wn, tile.ntile, (int)ntiles.d);
+  } else {
+    if constexpr (BM != 64) epilogue_load<MT, NT>(p, epi_in, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo);
+    epilogue_store<MT, NT>(p, acc, epi_in, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo, tile.split,
+                           lnrow + wm * WTM * 2, red + wm * WTM * 2, wn, tile.ntile, (int)ntiles.d);
+  }
 }
 
 // split-K finalize: sum of the partials (fp32 [splitk][M][N]) -> out with the epilogue of the main kernel
@@ -814,11 +907,11 @@ template <int BM, int BN, int NSETS> void launch_cfg(const IgemmParams& p, hipSt
   }
 }
 
-template <int BM, int BN, int NBUF> void launch_dma(const IgemmParams& p, hipStream_t s) {
-  constexpr int LDS = NBUF * (BM + BN) * 128 + BM * 16;   // stages, then two [BM][2] float arrays of row statistics
+template <int BM, int BN, int NBUF, bool ONEBAR = false, int KG = 1> void launch_dma(const IgemmParams& p, hipStream_t s) {
+  constexpr int LDS = KG * NBUF * (BM + BN) * 128 + BM * 16;   // stages, then two [BM][2] float arrays of row statistics
   static bool attr_set = false;
   if (!attr_set) {
-    hipFuncSetAttribute((const void*)igemm_dma_kernel<BM, BN, NBUF>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    hipFuncSetAttribute((const void*)igemm_dma_kernel<BM, BN, NBUF, ONEBAR, KG>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     attr_set = true;
   }
   const int mtiles = (p.M + BM - 1) / BM, ntiles = (p.N + BN - 1) / BN;
@@ -827,7 +920,7 @@ template <int BM, int BN, int NBUF> void launch_dma(const IgemmParams& p, hipStr
   const int splitk = p.splitk > 1 ? p.splitk : 1;
   const int sps = (total_stages + splitk - 1) / splitk;
   dim3 grid((mtiles * ntiles * splitk + 7) & ~7);
-  hipLaunchKernelGGL((igemm_dma_kernel<BM, BN, NBUF>), grid, dim3(256), LDS, s, p, make_fastdiv(mtiles),
+  hipLaunchKernelGGL((igemm_dma_kernel<BM, BN, NBUF, ONEBAR, KG>), grid, dim3(256 * KG), LDS, s, p, make_fastdiv(mtiles),
                      make_fastdiv(ntiles), ksteps_total, sps);
   if (splitk > 1) {
     long long total4 = (long long)p.M * p.N / 4;
@@ -925,10 +1018,43 @@ Choice choose(const IgemmParams& p) {
   return c;
 }
 
+template <int BM, int BN> int dma_blocks(const IgemmParams& p) {
+  return ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN) * (p.splitk > 1 ? p.splitk : 1);
+}
+
+// Pipeline shape per launch.  With more than one block per compute unit: two LDS buffers and two barriers per stage
+// (two co-resident blocks overlap each other's waits).  With at most one block per unit, or when two blocks of three
+// buffers still fit a unit's LDS (registers allow two): three buffers and one barrier per stage.  With at most one
+// block per unit and a long K range per block: eight waves in two groups that split the block's stages (in-block
+// split-K), which gives the unit two waves per SIMD; below ~24 stages the exchange of the accumulators at the end
+// costs more than that brings (per-layer timings inside the step: -2 to -9 us on the 3x3 layers of 40-75 us,
+// +1 us on the 13-19 us layers).  Launches of two blocks per unit stay as they are: two independent blocks beat
+// one grouped block after the other (48 -> 58 us).
+constexpr int kGroupSplitMinStages = 24;
+template <int BM, int BN> void launch_ring(const IgemmParams& p, hipStream_t s) {
+  constexpr int LDS3 = 3 * (BM + BN) * 128 + BM * 16;
+  const bool one_per_unit = dma_blocks<BM, BN>(p) <= 256;
+  bool three = 2 * LDS3 <= 160 * 1024 || one_per_unit;
+  int group_min = kGroupSplitMinStages;
+#ifdef SDSTREAM_DEVHOOKS
+  if (p.dev_exp & 16) three = false;
+  if (p.dev_exp & 32) three = true;
+  static const char* const kg = getenv("SDSTREAM_KGMIN");
+  if (kg) group_min = atoi(kg);
+#endif
+  if constexpr (BM == 128) {
+    const int splitk = p.splitk > 1 ? p.splitk : 1;
+    const int stages = (p.K / 64 + splitk - 1) / splitk;
+    if (one_per_unit && stages >= group_min) { launch_dma<BM, BN, 2, false, 2>(p, s); return; }
+  }
+  if (three) launch_dma<BM, BN, 3, true>(p, s);
+  else launch_dma<BM, BN, 2, false>(p, s);
+}
+
 template <int BN> void launch_bn(const IgemmParams& p, int variant, hipStream_t s) {
   switch (variant) {
-    case 1: launch_dma<128, BN, 2>(p, s); break;
-    case 2: launch_dma<64, BN, 2>(p, s); break;
+    case 1: launch_ring<128, BN>(p, s); break;
+    case 2: launch_ring<64, BN>(p, s); break;
     default: launch_cfg<128, BN, 3>(p, s); break;
   }
 }
