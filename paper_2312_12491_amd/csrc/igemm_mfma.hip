@@ -967,11 +967,15 @@ Choice choose(const IgemmParams& p) {
     if (fill(128) > fill(160) + 1e-3) bn6 = 128;
   }
   int sk = 1;
-  if (blocks(128, bn6) >= 200 && stages >= 5) {
+  const int nb6 = blocks(128, bn6);
+  // below 48 stages, where 64-row tiles alone fill the chip, they beat a two-way K split of 128-row tiles and its
+  // finalize pass (26 against 30 us on the 4096 x 640 x 2560 layers)
+  const bool no_split_64 = stages < 48 && blocks(64, bn0) >= 200;
+  if (nb6 >= 200 && stages >= 5) {
     c.variant = 1;
     c.bn = bn6;
-    sk = split_for(blocks(128, bn6));
-  } else if (stages >= 32) {
+    sk = split_for(nb6);
+  } else if (stages >= 32 && !no_split_64) {
     // long K, few tiles: split K; full tiles as long as enough blocks remain
     const int s1 = split_for(blocks(128, bn0));
     if (may_split && blocks(128, bn0) * s1 >= 150) {

@@ -126,6 +126,7 @@ __global__ __launch_bounds__(256) void conv_out4_bf16_kernel(const bf16_t* __res
                                                              const float* __restrict__ b, float* __restrict__ out, int N,
                                                              int H, int W, int C0) {
   typedef __attribute__((ext_vector_type(8))) __bf16 v8;
+  typedef __attribute__((ext_vector_type(2))) __bf16 v2;
   extern __shared__ __attribute__((aligned(16))) unsigned char wl[];  // [4][9][C0] bf16
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int chunks = C0 >> 3;
@@ -156,7 +157,8 @@ __global__ __launch_bounds__(256) void conv_out4_bf16_kernel(const bf16_t* __res
         for (int co = 0; co < 4; ++co) {
           const v8 wv = ((const v8*)wl)[(co * 9 + tap) * chunks + c];
 #pragma unroll
-          for (int e = 0; e < 8; ++e) acc[co] = fmaf((float)xv[tap][e], (float)wv[e], acc[co]);
+          for (int e = 0; e < 8; e += 2)   // v_dot2c_f32_bf16: two exact products and the sum in float, no conversions
+            acc[co] = __builtin_amdgcn_fdot2_f32_bf16(v2{xv[tap][e], xv[tap][e + 1]}, v2{wv[e], wv[e + 1]}, acc[co], false);
         }
     }
 #pragma unroll
