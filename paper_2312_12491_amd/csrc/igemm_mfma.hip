@@ -860,6 +860,138 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void igemm_dma_kernel(Ig
   }
 }
 
+// Kernel for wide 1x1 layers with a short K on many rows (K = 32 KSTEPS channels; the GEGLU input and fused q/k/v
+// projections of the first level): the block's 128 input rows stay in LDS for the whole launch (loaded once, against
+// once per column tile in the kernel above), and the weights never touch LDS - every wave owns 32-column slices of
+// the block's column range and reads its two packed fragments per k-step straight from global memory into a ring of
+// registers five k-steps deep.  After the prologue nothing synchronises: eight waves (two per SIMD) run at their own
+// pace, so one wave's epilogue overlaps the others' MFMAs.
+template <int KSTEPS, int RING>
+__global__ __launch_bounds__(512, 1) void igemm_rows_kernel(IgemmParams p, int nsplit, int slices_per_block) {
+  constexpr int BM = 128, MT = BM / 16, NT = 2;
+  static_assert(KSTEPS % RING == 0 && KSTEPS % 2 == 0, "the ring keeps its phase from slice to slice");
+  constexpr int STAGES = KSTEPS / 2;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];   // [STAGES][BM rows of 128 bytes, chunks XOR-swizzled]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int mtile = blockIdx.x / nsplit, ns = blockIdx.x - mtile * nsplit;
+  const int m0 = mtile * BM;
+  const int HWo = p.Hout * p.Wout;
+  const unsigned lds0 = (unsigned)(unsigned long long)(__attribute__((address_space(3))) void*)lds;
+  float* lnrow = (float*)(lds + STAGES * BM * 128);
+  const int K = KSTEPS * 32;
+
+  // the rows: STAGES x 16 loads of 1 KB (8 rows of 64 channels each), dealt over the eight waves
+  {
+    const char* A = (const char*)p.src1;
+    const char* zeros = (const char*)p.zeros;
+    for (int i = wave; i < STAGES * (BM / 8); i += 8) {
+      const int st = i / (BM / 8), rg = i - st * (BM / 8);
+      const int row = rg * 8 + (lane >> 3);
+      const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+      const int m = m0 + row;
+      const char* g = m < p.M ? A + ((long long)m * K + st * 64 + chunk * 8) * 2 : zeros;
+      lds_dma16(g, lds0 + st * (BM * 128) + rg * 1024);
+    }
+  }
+  ln_rows_to_lds(p, m0, BM, lnrow);
+
+  // this wave's slices: s_lo + wave, s_lo + wave + 8, ... below s_hi; slice = 32 columns = two packed n-tiles
+  const int s_lo = ns * slices_per_block;
+  const int s_hi = min(s_lo + slices_per_block, p.N >> 5);
+  const char* W = (const char*)p.W;
+  auto frag_ptr = [&](int slice, int t, int ks) {
+    return (const bf16x8*)(W + (((long long)(slice * 2 + t) * KSTEPS + ks) * 64 + lane) * 16);
+  };
+  bf16x8 bq[RING][NT];
+  int slice = s_lo + wave;
+  if (slice < s_hi) {
+#pragma unroll
+    for (int r = 0; r < RING; ++r)
+#pragma unroll
+      for (int t = 0; t < NT; ++t) bq[r][t] = *frag_ptr(slice, t, r);
+  }
+  int a_off[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) a_off[mt] = (mt * 16 + (lane & 15)) * 128;
+  const int a_x = ((lane & 15) >> 1) & 7;   // (row >> 1) & 7 with row = mt * 16 + lane % 16
+  __builtin_amdgcn_s_waitcnt(0x0F70 | 0 | (0 << 14));   // vmcnt(0): the rows (and the first fragments) have landed
+  __syncthreads();
+
+  for (; slice < s_hi; slice += 8) {
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int next = slice + 8;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      bf16x8 af[MT];
+      const unsigned char* sa = lds + (ks >> 1) * (BM * 128);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) af[mt] = *(const bf16x8*)(sa + a_off[mt] + (((((ks & 1) * 4) + (lane >> 4)) ^ a_x) << 4));
+      bf16x8 b0 = bq[ks % RING][0], b1 = bq[ks % RING][1];
+      // refill the ring slot with the k-step RING ahead: of this slice, or of the wave's next one
+      if (ks + RING < KSTEPS) {
+        bq[ks % RING][0] = *frag_ptr(slice, 0, ks + RING);
+        bq[ks % RING][1] = *frag_ptr(slice, 1, ks + RING);
+      } else if (next < s_hi) {
+        bq[ks % RING][0] = *frag_ptr(next, 0, ks + RING - KSTEPS);
+        bq[ks % RING][1] = *frag_ptr(next, 1, ks + RING - KSTEPS);
+      }
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        acc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b0, af[mt], acc[mt][0], 0, 0, 0);
+        acc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b1, af[mt], acc[mt][1], 0, 0, 0);
+      }
+      // Keeps the scheduler from hoisting every k-step's row fragments (spills).  A second fragment set, read under
+      // the previous k-step's MFMAs, was slower (37 against 33 us per launch): with two waves per SIMD the other
+      // wave already fills the wait.
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // epilogue of this kernel's layers: folded LayerNorm, bias, then GEGLU (value and gate tiles side by side) or plain
+    const int ncol = (lane >> 4) * 4;
+    const int n0 = slice * 32 + ncol, n1 = n0 + 16;
+    const float* zf = (const float*)p.zeros;
+    const f32x4 bias0 = *(const f32x4*)(p.bias ? p.bias + n0 : zf), bias1 = *(const f32x4*)(p.bias ? p.bias + n1 : zf);
+    const f32x4 ws0 = *(const f32x4*)(p.ln_wsum ? p.ln_wsum + n0 : zf), ws1 = *(const f32x4*)(p.ln_wsum ? p.ln_wsum + n1 : zf);
+    bf16_t* out = (bf16_t*)p.out;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int r = mt * 16 + (lane & 15), m = m0 + r;
+      f32x4 x0 = acc[mt][0], x1 = acc[mt][1];
+      if (p.ln_stats) {
+        const float mean = lnrow[r * 2], rstd = lnrow[r * 2 + 1];
+        x0 = (x0 - mean * ws0) * rstd;
+        x1 = (x1 - mean * ws1) * rstd;
+      }
+      x0 += bias0;
+      x1 += bias1;
+      if (m >= p.M) continue;
+      if (p.epilogue == EPI_GEGLU) {
+        bf16x4 o;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) o[v] = (bf16_t)(x0[v] * gelu_erf(x1[v]));
+#ifdef SDSTREAM_DEVHOOKS
+        if (p.dev_exp & 1) {
+#pragma unroll
+          for (int v = 0; v < 4; ++v) o[v] = (bf16_t)(x0[v] * x1[v]);
+        }
+        if ((p.dev_exp & 2) && x0[0] != 12345.678f) continue;
+#endif
+        *(bf16x4*)(out + (long long)m * (p.N >> 1) + slice * 16 + ncol) = o;
+      } else {
+        bf16x4 o0, o1;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) { o0[v] = (bf16_t)x0[v]; o1[v] = (bf16_t)x1[v]; }
+        *(bf16x4*)(out + (long long)m * p.N + n0) = o0;
+        *(bf16x4*)(out + (long long)m * p.N + n1) = o1;
+      }
+    }
+  }
+}
+
 // split-K finalize: sum of the partials (fp32 [splitk][M][N]) -> out with the epilogue of the main kernel
 __global__ __launch_bounds__(256) void igemm_finalize_kernel(IgemmParams p) {
   const long long idx4 = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -926,6 +1058,32 @@ template <int BM, int BN, int NBUF, bool ONEBAR = false, int KG = 1> void launch
     long long total4 = (long long)p.M * p.N / 4;
     hipLaunchKernelGGL(igemm_finalize_kernel, dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s, p);
   }
+}
+
+// the layers igemm_rows_kernel takes: plain rows (1x1, one source), K = 320, no row statistics to leave, and enough
+// rows and columns that 256 blocks of eight waves all have work
+bool rows_kernel_fits(const IgemmParams& p) {
+  if (p.ksize != 1 || p.stride != 1 || p.upsample || p.C2 != 0 || p.C3 != 0 || p.C1 != 320) return false;
+  if (p.epilogue != EPI_NONE && p.epilogue != EPI_GEGLU) return false;
+  if (p.stats_out || p.slot_m > 0 || p.force_bn || p.residual || p.rowbias) return false;
+  if (p.N % 32 || p.N < 960) return false;
+  const int mtiles = (p.M + 127) / 128;
+  return mtiles >= 100;
+}
+
+void launch_rows(const IgemmParams& p, hipStream_t s) {
+  constexpr int KSTEPS = 10;
+  constexpr int LDS = (KSTEPS / 2) * 128 * 128 + 128 * 16;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipFuncSetAttribute((const void*)igemm_rows_kernel<KSTEPS, 5>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    attr_set = true;
+  }
+  const int mtiles = (p.M + 127) / 128;
+  const int nsplit = mtiles >= 256 ? 1 : 256 / mtiles;
+  const int slices = p.N / 32;
+  const int spb = (slices + nsplit - 1) / nsplit;
+  hipLaunchKernelGGL((igemm_rows_kernel<KSTEPS, 5>), dim3(mtiles * nsplit), dim3(512), LDS, s, p, nsplit, spb);
 }
 
 struct Choice { int variant, bn, splitk; };  // variant 0: 32-deep stages, weights through registers (any C % 32 == 0);
@@ -1110,7 +1268,12 @@ void launch_igemm_mfma(const IgemmParams& p0, hipStream_t s) {
   p.fd_ct = make_fastdiv((unsigned)(p.C1 + p.C2));
   p.fd_ks = make_fastdiv((unsigned)p.ksize);
   p.fd_n = make_fastdiv((unsigned)p.N);
-  if (c.bn == 160) launch_bn<160>(p, c.variant, s);
+  bool rows = c.variant == 1 && c.splitk == 1 && rows_kernel_fits(p);
+#ifdef SDSTREAM_DEVHOOKS
+  if (p.dev_exp & 64) rows = false;
+#endif
+  if (rows) launch_rows(p, s);
+  else if (c.bn == 160) launch_bn<160>(p, c.variant, s);
   else if (c.bn == 128) launch_bn<128>(p, c.variant, s);
   else launch_bn<64>(p, c.variant, s);
 }

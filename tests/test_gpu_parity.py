@@ -59,6 +59,12 @@ def test_unet_mini_bf16(name):
     check_bf16(got, want, name)
 
 
+def test_unet_wide_first_level_with_a_ragged_row_tile_bf16():
+    # 4 rows x 60 x 60 pixels x 320 channels: the row-resident GEMM kernel of the wide 1x1 layers, last row tile half full
+    got, want = _unet_case(MINI_CONFIGS["wide320"], "bf16", 4, [999, 759, 499, 259])
+    check_bf16(got, want, "wide320")
+
+
 @pytest.mark.parametrize("name,dtype", [("mini15", "fp32"), ("mini40", "fp32"), ("mini15", "bf16"), ("mini21", "bf16"),
                                         ("mini40", "bf16")])
 def test_unet_mini_with_random_norm_scales_and_shifts(name, dtype):
