@@ -698,10 +698,19 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void igemm_dma_kernel(Ig
 #pragma unroll
     for (int i = 0; i < NLA; ++i) {
       const char* g = okv[i] ? aptr[i] : zeros;
+#ifdef SDSTREAM_DEVHOOKS
+      if (p.dev_exp & 256) g = zeros;
+#endif
       lds_dma16(g, sa + (i * NW + wave) * 1024);
     }
 #pragma unroll
-    for (int i = 0; i < NLB; ++i) lds_dma16(bptr[i], sa + ABYTES + (i * NW + wave) * 1024);
+    for (int i = 0; i < NLB; ++i) {
+      const char* g = bptr[i];
+#ifdef SDSTREAM_DEVHOOKS
+      if (p.dev_exp & 512) g = zeros;
+#endif
+      lds_dma16(g, sa + ABYTES + (i * NW + wave) * 1024);
+    }
 #pragma unroll
     for (int g = 0; g < KG; ++g) advance();
   };
@@ -736,6 +745,9 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void igemm_dma_kernel(Ig
   // stage's first k-step, so half of the LDS read latency sits in the shadow of the matrix cores.
   bf16x8 af[2][MT], bfr[2][NT];
   auto read_frags = [&](int ks, int buf) {
+#ifdef SDSTREAM_DEVHOOKS
+    if ((p.dev_exp & 1024) && (ks | buf) != 0) return;
+#endif
     const unsigned char* sa = ring + buf * STAGE;
     const unsigned char* sb = sa + ABYTES;
 #pragma unroll
