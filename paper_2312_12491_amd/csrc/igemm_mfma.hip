@@ -554,7 +554,7 @@ template <int BM, int BN, int NBUF, bool ONEBAR, int KG>
 __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void igemm_dma_kernel(IgemmParams p, FastDiv mtiles,
                                                                              FastDiv ntiles, int ksteps_total,
                                                                              int stages_per_split) {
-  static_assert(KG == 1 || (KG == 2 && NBUF == 2 && !ONEBAR && BM == 128), "two wave groups: two buffers each, 128 rows");
+  static_assert(KG == 1 || (KG == 2 && NBUF == 2 && !ONEBAR), "two wave groups: two buffers each");
   constexpr int WM = 2, WN = 2, NW = 4;
   constexpr int WTM = BM / WM, WTN = BN / WN, MT = WTM / 16, NT = WTN / 16;
   constexpr int NLA = BM / 8 / NW, NLB = BN / 8 / NW;   // 1 KB loads per wave and stage: activation row groups, weight fragments
@@ -733,7 +733,7 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void igemm_dma_kernel(Ig
   // 64-row tiles (the short-K layers): what the epilogue reads is requested ahead of the main loop.  These
   // loads are older than every LDS load below, so the first stage's vmcnt wait covers them.
   EpilogueIn<MT, NT> epi_in;
-  if constexpr (BM == 64) epilogue_load<MT, NT>(p, epi_in, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo);
+  if constexpr (BM == 64 && KG == 1) epilogue_load<MT, NT>(p, epi_in, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo);
   constexpr int PRE = ONEBAR ? NBUF - 1 : NBUF;   // stages in flight ahead of the one being multiplied
 #pragma unroll
   for (int b = 0; b < PRE; ++b)
@@ -872,15 +872,17 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void igemm_dma_kernel(Ig
   }
 }
 
-// Kernel for wide 1x1 layers with a short K on many rows (K = 32 KSTEPS channels; the GEGLU input and fused q/k/v
-// projections of the first level): the block's 128 input rows stay in LDS for the whole launch (loaded once, against
-// once per column tile in the kernel above), and the weights never touch LDS - every wave owns 32-column slices of
-// the block's column range and reads its two packed fragments per k-step straight from global memory into a ring of
-// registers five k-steps deep.  After the prologue nothing synchronises: eight waves (two per SIMD) run at their own
-// pace, so one wave's epilogue overlaps the others' MFMAs.
-template <int KSTEPS, int RING>
-__global__ __launch_bounds__(512, 1) void igemm_rows_kernel(IgemmParams p, int nsplit, int slices_per_block) {
-  constexpr int BM = 128, MT = BM / 16, NT = 2;
+// Kernel for 1x1 layers with a short K on many rows (K = 32 KSTEPS channels): the block's BM input rows stay in LDS
+// for the whole launch (loaded once, against once per column tile in the kernel above), and the weights never touch
+// LDS - every wave owns 32-column slices of the block's column range and reads its two packed fragments per k-step
+// straight from global memory into a ring of registers five k-steps deep.  After the prologue nothing synchronises:
+// the waves (two or more per SIMD) run at their own pace, so one wave's epilogue overlaps the others' MFMAs.
+// Two shapes: 128 rows x 8 waves walking many slices each (GEGLU input, fused q/k/v of the first level), and
+// 64 rows x 10 waves with one slice each for N = 320 (the projections around the attentions of the first level),
+// where the waves meet once at the end to add up the row statistics a following folded LayerNorm reads.
+template <int KSTEPS, int BM, int WAVES>
+__global__ __launch_bounds__(64 * WAVES, 1) void igemm_rows_kernel(IgemmParams p, int nsplit, int slices_per_block) {
+  constexpr int MT = BM / 16, NT = 2, RING = 5;
   static_assert(KSTEPS % RING == 0 && KSTEPS % 2 == 0, "the ring keeps its phase from slice to slice");
   constexpr int STAGES = KSTEPS / 2;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];   // [STAGES][BM rows of 128 bytes, chunks XOR-swizzled]
@@ -888,16 +890,18 @@ __global__ __launch_bounds__(512, 1) void igemm_rows_kernel(IgemmParams p, int n
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int mtile = blockIdx.x / nsplit, ns = blockIdx.x - mtile * nsplit;
   const int m0 = mtile * BM;
-  const int HWo = p.Hout * p.Wout;
   const unsigned lds0 = (unsigned)(unsigned long long)(__attribute__((address_space(3))) void*)lds;
-  float* lnrow = (float*)(lds + STAGES * BM * 128);
+  float* lnrow = (float*)(lds + STAGES * BM * 128);   // [BM][2] mean, rstd of the input rows (folded LayerNorm)
+  float* red = lnrow + BM * 2;                        // [WAVES][BM][2] row statistics per wave
   const int K = KSTEPS * 32;
+  const bool slot1 = p.slot_m > 0 && m0 >= p.slot_m;  // rows of the second prompt: second set of weights and vectors
+  const long long voff = slot1 ? p.slot_v_bytes / 4 : 0;
 
-  // the rows: STAGES x 16 loads of 1 KB (8 rows of 64 channels each), dealt over the eight waves
+  // the rows: STAGES x BM/8 loads of 1 KB (8 rows of 64 channels each), dealt over the waves
   {
     const char* A = (const char*)p.src1;
     const char* zeros = (const char*)p.zeros;
-    for (int i = wave; i < STAGES * (BM / 8); i += 8) {
+    for (int i = wave; i < STAGES * (BM / 8); i += WAVES) {
       const int st = i / (BM / 8), rg = i - st * (BM / 8);
       const int row = rg * 8 + (lane >> 3);
       const int chunk = (lane & 7) ^ ((row >> 1) & 7);
@@ -908,10 +912,10 @@ __global__ __launch_bounds__(512, 1) void igemm_rows_kernel(IgemmParams p, int n
   }
   ln_rows_to_lds(p, m0, BM, lnrow);
 
-  // this wave's slices: s_lo + wave, s_lo + wave + 8, ... below s_hi; slice = 32 columns = two packed n-tiles
+  // this wave's slices: s_lo + wave, s_lo + wave + WAVES, ... below s_hi; slice = 32 columns = two packed n-tiles
   const int s_lo = ns * slices_per_block;
   const int s_hi = min(s_lo + slices_per_block, p.N >> 5);
-  const char* W = (const char*)p.W;
+  const char* W = (const char*)p.W + (slot1 ? p.slot_w_bytes : 0);
   auto frag_ptr = [&](int slice, int t, int ks) {
     return (const bf16x8*)(W + (((long long)(slice * 2 + t) * KSTEPS + ks) * 64 + lane) * 16);
   };
@@ -930,13 +934,37 @@ __global__ __launch_bounds__(512, 1) void igemm_rows_kernel(IgemmParams p, int n
   __builtin_amdgcn_s_waitcnt(0x0F70 | 0 | (0 << 14));   // vmcnt(0): the rows (and the first fragments) have landed
   __syncthreads();
 
-  for (; slice < s_hi; slice += 8) {
+  const int ncol = (lane >> 4) * 4;
+  const float* zf = (const float*)p.zeros;
+  bf16_t* out = (bf16_t*)p.out;
+  const bf16_t* res = (const bf16_t*)p.residual;
+  for (; slice < s_hi; slice += WAVES) {
     f32x4 acc[MT][NT];
 #pragma unroll
     for (int i = 0; i < MT; ++i)
 #pragma unroll
       for (int j = 0; j < NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const int next = slice + 8;
+    const int next = slice + WAVES;
+    const int n0 = slice * 32 + ncol, n1 = n0 + 16;
+    // what the epilogue reads is requested ahead of the loop: bias and weight row sums (16 registers), and the
+    // residual of the short shape (16 more; the tall shape has none)
+    const f32x4 bias0 = *(const f32x4*)(p.bias ? p.bias + voff + n0 : zf), bias1 = *(const f32x4*)(p.bias ? p.bias + voff + n1 : zf);
+    f32x4 ws0 = {0.f, 0.f, 0.f, 0.f}, ws1 = ws0;
+    if constexpr (BM == 128) {   // (only the tall shape takes layers with a folded LayerNorm)
+      ws0 = *(const f32x4*)(p.ln_wsum ? p.ln_wsum + voff + n0 : zf);
+      ws1 = *(const f32x4*)(p.ln_wsum ? p.ln_wsum + voff + n1 : zf);
+    }
+    bf16x4 r0[MT], r1[MT];
+    if constexpr (BM == 64) {
+      if (res) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const int m = min(m0 + mt * 16 + (lane & 15), p.M - 1);
+          r0[mt] = *(const bf16x4*)(res + (long long)m * p.N + n0);
+          r1[mt] = *(const bf16x4*)(res + (long long)m * p.N + n1);
+        }
+      }
+    }
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) {
       bf16x8 af[MT];
@@ -962,43 +990,79 @@ __global__ __launch_bounds__(512, 1) void igemm_rows_kernel(IgemmParams p, int n
       // wave already fills the wait.
       __builtin_amdgcn_sched_barrier(0);
     }
-    // epilogue of this kernel's layers: folded LayerNorm, bias, then GEGLU (value and gate tiles side by side) or plain
-    const int ncol = (lane >> 4) * 4;
-    const int n0 = slice * 32 + ncol, n1 = n0 + 16;
-    const float* zf = (const float*)p.zeros;
-    const f32x4 bias0 = *(const f32x4*)(p.bias ? p.bias + n0 : zf), bias1 = *(const f32x4*)(p.bias ? p.bias + n1 : zf);
-    const f32x4 ws0 = *(const f32x4*)(p.ln_wsum ? p.ln_wsum + n0 : zf), ws1 = *(const f32x4*)(p.ln_wsum ? p.ln_wsum + n1 : zf);
-    bf16_t* out = (bf16_t*)p.out;
+    // epilogue of this kernel's layers: folded LayerNorm, bias, then GEGLU (value and gate tiles side by side) or
+    // residual and plain store, with the row sums of what is stored for a LayerNorm folded into the next layer
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       const int r = mt * 16 + (lane & 15), m = m0 + r;
       f32x4 x0 = acc[mt][0], x1 = acc[mt][1];
-      if (p.ln_stats) {
-        const float mean = lnrow[r * 2], rstd = lnrow[r * 2 + 1];
-        x0 = (x0 - mean * ws0) * rstd;
-        x1 = (x1 - mean * ws1) * rstd;
+      if constexpr (BM == 128) {
+        if (p.ln_stats) {
+          const float mean = lnrow[r * 2], rstd = lnrow[r * 2 + 1];
+          x0 = (x0 - mean * ws0) * rstd;
+          x1 = (x1 - mean * ws1) * rstd;
+        }
       }
       x0 += bias0;
       x1 += bias1;
-      if (m >= p.M) continue;
-      if (p.epilogue == EPI_GEGLU) {
-        bf16x4 o;
+      float ssum = 0.f, ssq = 0.f;
+      if (m < p.M) {
+        if (p.epilogue == EPI_GEGLU) {
+          bf16x4 o;
 #pragma unroll
-        for (int v = 0; v < 4; ++v) o[v] = (bf16_t)(x0[v] * gelu_erf(x1[v]));
+          for (int v = 0; v < 4; ++v) o[v] = (bf16_t)(x0[v] * gelu_erf(x1[v]));
 #ifdef SDSTREAM_DEVHOOKS
-        if (p.dev_exp & 1) {
+          if (p.dev_exp & 1) {
 #pragma unroll
-          for (int v = 0; v < 4; ++v) o[v] = (bf16_t)(x0[v] * x1[v]);
-        }
-        if ((p.dev_exp & 2) && x0[0] != 12345.678f) continue;
+            for (int v = 0; v < 4; ++v) o[v] = (bf16_t)(x0[v] * x1[v]);
+          }
+          if ((p.dev_exp & 2) && x0[0] != 12345.678f) continue;
 #endif
-        *(bf16x4*)(out + (long long)m * (p.N >> 1) + slice * 16 + ncol) = o;
-      } else {
-        bf16x4 o0, o1;
+          *(bf16x4*)(out + (long long)m * (p.N >> 1) + slice * 16 + ncol) = o;
+        } else {
+          if constexpr (BM == 64) {
+            if (res) {
 #pragma unroll
-        for (int v = 0; v < 4; ++v) { o0[v] = (bf16_t)x0[v]; o1[v] = (bf16_t)x1[v]; }
-        *(bf16x4*)(out + (long long)m * p.N + n0) = o0;
-        *(bf16x4*)(out + (long long)m * p.N + n1) = o1;
+              for (int v = 0; v < 4; ++v) { x0[v] += (float)r0[mt][v]; x1[v] += (float)r1[mt][v]; }
+            }
+          }
+          bf16x4 o0, o1;
+#pragma unroll
+          for (int v = 0; v < 4; ++v) { o0[v] = (bf16_t)x0[v]; o1[v] = (bf16_t)x1[v]; }
+          *(bf16x4*)(out + (long long)m * p.N + n0) = o0;
+          *(bf16x4*)(out + (long long)m * p.N + n1) = o1;
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const float a = (float)o0[v], b = (float)o1[v];
+            ssum += a + b;
+            ssq = fmaf(a, a, fmaf(b, b, ssq));
+          }
+        }
+      }
+      if constexpr (BM == 64) {
+        if (p.stats_out) {   // block-uniform
+          ssum = quad_sum(ssum);
+          ssq = quad_sum(ssq);
+          if (lane < 16) {
+            red[(wave * BM + r) * 2] = ssum;
+            red[(wave * BM + r) * 2 + 1] = ssq;
+          }
+        }
+      }
+    }
+  }
+  if constexpr (BM == 64) {
+    // every wave of the short shape has exactly one slice (the launcher sees to it), so all of them arrive here
+    if (p.stats_out) {
+      __syncthreads();
+      if (tid < BM && m0 + tid < p.M) {
+        float2 o = {0.f, 0.f};
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) {
+          o.x += red[(w * BM + tid) * 2];
+          o.y += red[(w * BM + tid) * 2 + 1];
+        }
+        *((float2*)p.stats_out + (m0 + tid)) = o;   // one part per row
       }
     }
   }
@@ -1072,34 +1136,47 @@ template <int BM, int BN, int NBUF, bool ONEBAR = false, int KG = 1> void launch
   }
 }
 
-// the layers igemm_rows_kernel takes: plain rows (1x1, one source), K = 320, no row statistics to leave, and enough
-// rows and columns that 256 blocks of eight waves all have work
-bool rows_kernel_fits(const IgemmParams& p) {
-  if (p.ksize != 1 || p.stride != 1 || p.upsample || p.C2 != 0 || p.C3 != 0 || p.C1 != 320) return false;
-  if (p.epilogue != EPI_NONE && p.epilogue != EPI_GEGLU) return false;
-  if (p.stats_out || p.slot_m > 0 || p.force_bn || p.residual || p.rowbias) return false;
-  if (p.N % 32 || p.N < 960) return false;
-  const int mtiles = (p.M + 127) / 128;
-  return mtiles >= 100;
+// The layers igemm_rows_kernel takes: plain rows (1x1, one source), enough of them that 256 blocks have work, and
+//  tall shape: K = 320 and N >= 960, no residual, no row statistics to leave (GEGLU input, fused q/k/v);
+//  short shape: K = 320 or 640 and N = 320 (ten waves, one 32-column slice each).
+// Returns 0, or the shape (1 tall, 2 short).  Must not depend on the row range or the weight slot of a launch: a
+// layer launched on sub-ranges of its rows keeps the kernel chosen for the whole range (force_variant).
+int rows_kernel_shape(const IgemmParams& p) {
+  if (p.ksize != 1 || p.stride != 1 || p.upsample || p.C2 != 0 || p.C3 != 0 || p.rowbias || p.N % 32) return 0;
+  if (p.epilogue == EPI_GEGLU || (p.epilogue == EPI_NONE && p.N >= 960)) {
+    if (p.C1 != 320 || p.stats_out || p.residual) return 0;
+    return (p.M + 127) / 128 >= 100 ? 1 : 0;
+  }
+  if (p.epilogue == EPI_NONE && p.N == 320 && (p.C1 == 320 || p.C1 == 640) && !p.ln_stats)
+    return (p.M + 63) / 64 >= 200 ? 2 : 0;
+  return 0;
+}
+
+template <int KSTEPS, int BM, int WAVES> void launch_rows_t(const IgemmParams& p, int nsplit, hipStream_t s) {
+  constexpr int LDS = (KSTEPS / 2) * BM * 128 + BM * 8 + WAVES * BM * 8;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipFuncSetAttribute((const void*)igemm_rows_kernel<KSTEPS, BM, WAVES>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    attr_set = true;
+  }
+  const int mtiles = (p.M + BM - 1) / BM;
+  const int slices = p.N / 32;
+  const int spb = (slices + nsplit - 1) / nsplit;
+  hipLaunchKernelGGL((igemm_rows_kernel<KSTEPS, BM, WAVES>), dim3(mtiles * nsplit), dim3(64 * WAVES), LDS, s, p, nsplit, spb);
 }
 
 void launch_rows(const IgemmParams& p, hipStream_t s) {
-  constexpr int KSTEPS = 10;
-  constexpr int LDS = (KSTEPS / 2) * 128 * 128 + 128 * 16;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipFuncSetAttribute((const void*)igemm_rows_kernel<KSTEPS, 5>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-    attr_set = true;
+  if (p.N == 320 && p.epilogue == EPI_NONE) {   // short shape: ten slices, one per wave
+    if (p.C1 == 320) launch_rows_t<10, 64, 10>(p, 1, s); else launch_rows_t<20, 64, 10>(p, 1, s);
+    return;
   }
   const int mtiles = (p.M + 127) / 128;
-  const int nsplit = mtiles >= 256 ? 1 : 256 / mtiles;
-  const int slices = p.N / 32;
-  const int spb = (slices + nsplit - 1) / nsplit;
-  hipLaunchKernelGGL((igemm_rows_kernel<KSTEPS, 5>), dim3(mtiles * nsplit), dim3(512), LDS, s, p, nsplit, spb);
+  launch_rows_t<10, 128, 8>(p, mtiles >= 256 ? 1 : 256 / mtiles, s);
 }
 
 struct Choice { int variant, bn, splitk; };  // variant 0: 32-deep stages, weights through registers (any C % 32 == 0);
-                                             // 1: direct-to-LDS kernel with 128-row tiles, 2: with 64-row tiles
+                                             // 1: direct-to-LDS kernel with 128-row tiles, 2: with 64-row tiles,
+                                             // 3: row-resident kernel (bn = N: one part of row statistics per row)
 
 // Tile / kernel / split-K selection, from per-layer timings of the SD-shaped net on MI355X (256 compute units).
 // What the timings say: a layer runs best with about one 128-row tile per compute unit - 256 blocks beat 512 blocks
@@ -1118,6 +1195,23 @@ Choice choose(const IgemmParams& p) {
     c.variant = 0;
     if (p.stats_out && (p.N + c.bn - 1) / c.bn > LN_MAX_PARTS) c.bn = 160;
     return c;
+  }
+  if (!p.force_bn) {
+    bool rows_ok = true;
+#ifdef SDSTREAM_DEVHOOKS
+    static const bool no_rows = getenv("SDSTREAM_NO_ROWS") != nullptr;   // (read here: the engine asks for plans too)
+    static const bool no_rows_short = getenv("SDSTREAM_NO_ROWS_SHORT") != nullptr;
+    rows_ok = !no_rows;
+#endif
+    int shape = rows_ok ? rows_kernel_shape(p) : 0;
+#ifdef SDSTREAM_DEVHOOKS
+    if (shape == 2 && no_rows_short) shape = 0;
+#endif
+    if (shape) {
+      c.variant = 3;
+      c.bn = shape == 2 ? p.N : bn0;
+      return c;
+    }
   }
   const int stages = p.K / 64;
   const bool may_split = p.epilogue == EPI_NONE && p.workspace != nullptr && !p.no_splitk;
@@ -1203,7 +1297,8 @@ template <int BM, int BN> int dma_blocks(const IgemmParams& p) {
 // split-K), which gives the unit two waves per SIMD; below ~24 stages the exchange of the accumulators at the end
 // costs more than that brings (per-layer timings inside the step: -2 to -9 us on the 3x3 layers of 40-75 us,
 // +1 us on the 13-19 us layers).  Launches of two blocks per unit stay as they are: two independent blocks beat
-// one grouped block after the other (48 -> 58 us).
+// one grouped block after the other (48 -> 58 us); launches of 16-160 blocks on the deep levels gain nothing from
+// groups either (+-0.5 us: their 12-19 us are launch, prologue and epilogue latency, not the loop).
 constexpr int kGroupSplitMinStages = 24;
 template <int BM, int BN> void launch_ring(const IgemmParams& p, hipStream_t s) {
   constexpr int LDS3 = 3 * (BM + BN) * 128 + BM * 16;
@@ -1241,7 +1336,7 @@ IgemmPlan igemm_mfma_plan(const IgemmParams& p) {
   const Choice c = choose(p);
   IgemmPlan r;
   r.variant = c.variant;
-  r.bm = c.variant == 2 ? 64 : 128;
+  r.bm = c.variant == 2 || (c.variant == 3 && p.N == 320 && p.epilogue == EPI_NONE) ? 64 : 128;
   r.bn = c.bn;
   r.splitk = c.splitk;
   if (r.splitk > 1) {  // drop splits that the rounding of stages per split leaves empty
@@ -1280,11 +1375,7 @@ void launch_igemm_mfma(const IgemmParams& p0, hipStream_t s) {
   p.fd_ct = make_fastdiv((unsigned)(p.C1 + p.C2));
   p.fd_ks = make_fastdiv((unsigned)p.ksize);
   p.fd_n = make_fastdiv((unsigned)p.N);
-  bool rows = c.variant == 1 && c.splitk == 1 && rows_kernel_fits(p);
-#ifdef SDSTREAM_DEVHOOKS
-  if (p.dev_exp & 64) rows = false;
-#endif
-  if (rows) launch_rows(p, s);
+  if (c.variant == 3) launch_rows(p, s);
   else if (c.bn == 160) launch_bn<160>(p, c.variant, s);
   else if (c.bn == 128) launch_bn<128>(p, c.variant, s);
   else launch_bn<64>(p, c.variant, s);
