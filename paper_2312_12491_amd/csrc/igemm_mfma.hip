@@ -1297,8 +1297,9 @@ template <int BM, int BN> int dma_blocks(const IgemmParams& p) {
 // split-K), which gives the unit two waves per SIMD; below ~24 stages the exchange of the accumulators at the end
 // costs more than that brings (per-layer timings inside the step: -2 to -9 us on the 3x3 layers of 40-75 us,
 // +1 us on the 13-19 us layers).  Launches of two blocks per unit stay as they are: two independent blocks beat
-// one grouped block after the other (48 -> 58 us); launches of 16-160 blocks on the deep levels gain nothing from
-// groups either (+-0.5 us: their 12-19 us are launch, prologue and epilogue latency, not the loop).
+// one grouped block after the other (48 -> 58 us); launches of 16-160 blocks on the deep levels and the 64-row
+// launches of one block per unit gain nothing from groups either (+-0.5 us: their 12-19 us are launch, prologue
+// and epilogue latency, not the loop).
 constexpr int kGroupSplitMinStages = 24;
 template <int BM, int BN> void launch_ring(const IgemmParams& p, hipStream_t s) {
   constexpr int LDS3 = 3 * (BM + BN) * 128 + BM * 16;
