@@ -60,9 +60,19 @@ def test_unet_mini_bf16(name):
 
 
 def test_unet_wide_first_level_with_a_ragged_row_tile_bf16():
-    # 4 rows x 60 x 60 pixels x 320 channels: the row-resident GEMM kernel of the wide 1x1 layers, last row tile half full
+    # 4 rows x 62 x 58 pixels x 320 channels: the row-resident GEMM kernels of the 1x1 layers, last row tile ragged
     got, want = _unet_case(MINI_CONFIGS["wide320"], "bf16", 4, [999, 759, 499, 259])
     check_bf16(got, want, "wide320")
+
+
+def test_stream_wide_first_level_full_cfg_bf16():
+    # two prompts on 2 + 2 rows of 3596 pixels: the boundary between them falls inside a row tile, so the folded
+    # cross-attention runs as two launches on row ranges, each with the kernel chosen for the whole range
+    wl = MINI_CONFIGS["wide320"]
+    worst_max, worst = _stream_case(wl, "bf16", 1, 1.2, 1.0, 3)
+    print(f"wide320 full CFG: rel_l2 {worst:.3e}, max|g-o|/max|o| {worst_max:.3e}")
+    assert worst <= TOL_BF16
+    assert worst_max <= TOL_BF16_MAX
 
 
 @pytest.mark.parametrize("name,dtype", [("mini15", "fp32"), ("mini40", "fp32"), ("mini15", "bf16"), ("mini21", "bf16"),

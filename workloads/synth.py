@@ -117,15 +117,15 @@ _MINI40 = dict(in_channels=4, block_channels=(160, 320, 640), layers_per_block=1
                attn_levels=(1, 1, 0), num_heads=4, head_dim=0, mid_attention=1,
                context_len=77, context_dim=192, norm_groups=32)
 
-# one wide level (320 channels on 4 x 60 x 60 = 14 400 pixels, a ragged number of 128-row tiles): the shape
+# one wide level (320 channels on 4 x 62 x 58 = 14 384 pixels, a ragged number of 64- and 128-row tiles): the shape
 # class of the first level of the SD nets, which some kernels are specialised for, at a size the oracle still finishes
 _WIDE320 = dict(in_channels=4, block_channels=(320, 640), layers_per_block=1,
                 attn_levels=(1, 0), num_heads=8, head_dim=0, mid_attention=0,
                 context_len=77, context_dim=128, norm_groups=32)
 
 MINI_CONFIGS = {
-    "wide320": dict(name="wide320", unet=_WIDE320, latent=(60, 60), init="fanin",
-                    timesteps=(999, 759, 499, 259), n_streams=1, seeds=_seeds(14)),
+    "wide320": dict(name="wide320", unet=_WIDE320, latent=(62, 58), init="fanin",
+                    timesteps=(999, 499), n_streams=1, seeds=_seeds(14)),
     "mini15": dict(name="mini15", unet=_MINI15, latent=(24, 40), init="fanin",
                    timesteps=(999, 759, 499, 259), n_streams=1, seeds=_seeds(11)),
     "mini21": dict(name="mini21", unet=_MINI21, latent=(16, 16), init="fanin",
