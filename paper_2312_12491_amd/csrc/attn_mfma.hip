@@ -42,7 +42,7 @@ __device__ __forceinline__ float quad_sum(float x) {
 // one, so row d of O^T accumulates the softmax denominator in the matrix core - from the same bf16-rounded
 // probabilities as the numerator, rescaled with it - and the per-tile sum on the vector ALU, which bounds this
 // kernel at small d, goes away.
-template <int DK, int DT, int QT, bool ONES>
+template <int DK, int DT, int QT, bool ONES, int PIPE>
 __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
   constexpr int BQ = 4 * QT * 16;
   constexpr int KPITCH = DK * 64 + 16;   // bytes per key row of the K tile
@@ -175,6 +175,97 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
     const bool more = j0 + BKV < Skv;
     if (more) load_tiles(j0 + BKV);  // in flight while this tile is multiplied
 
+    if constexpr (PIPE != 0) {
+      // Software pipeline over the wave's query tiles: the softmax of tile t (vector ALU, what bounds this kernel at
+      // small d) is issued interleaved with the matrix-core work that does not depend on it - the scores of tile
+      // t + 1 and the P V product of tile t - 1 - instead of three phases one after the other.  The tile's K fragments
+      // are read once into registers (every one serves all QT query tiles); scores and probabilities alternate
+      // between two register sets.
+      bf16x8 kfr[4][DK];
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int ks = 0; ks < DK; ++ks) kfr[kt][ks] = *(const bf16x8*)(Ks + (kt * 16 + li) * KPITCH + (ks * 32 + g * 8) * 2);
+      constexpr bool VPRE = DT * QT <= 12;
+      bf16x8 vfr[VPRE ? DT : 1][2];
+      if constexpr (VPRE) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+          for (int kk = 0; kk < 2; ++kk)
+            vfr[dt][kk] = *(const bf16x8*)(Vs + (dt * 16 + li) * VPITCH + (kk * 32 + g * 8) * 2);
+      }
+      f32x4 sacc[2][4];
+      bf16x8 pf[2][2];
+      auto scores = [&](int t, f32x4 (&sa)[4]) {
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt) {
+          sa[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int ks = 0; ks < DK; ++ks)
+            sa[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr[kt][ks], qf[t][ks], sa[kt], 0, 0, 0);
+        }
+      };
+      auto weighted_values = [&](int t, const bf16x8 (&pp)[2]) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+          for (int kk = 0; kk < 2; ++kk) {
+            bf16x8 vf;
+            if constexpr (VPRE) vf = vfr[dt][kk];
+            else vf = *(const bf16x8*)(Vs + (dt * 16 + li) * VPITCH + (kk * 32 + g * 8) * 2);
+            o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pp[kk], o[t][dt], 0, 0, 0);
+          }
+      };
+      scores(0, sacc[0]);
+      __builtin_amdgcn_sched_barrier(0);   // what follows is scheduled without these: they have nothing to hide behind
+#pragma unroll
+      for (int t = 0; t < QT; ++t) {
+        if (t + 1 < QT) scores(t + 1, sacc[(t + 1) & 1]);
+        if (t > 0) weighted_values(t - 1, pf[(t - 1) & 1]);
+        f32x4(&sa)[4] = sacc[t & 1];
+        if constexpr (RAGGED) {
+#pragma unroll
+          for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+              if (j0 + kt * 16 + g * 4 + v >= Skv) sa[kt][v] = -3.0e38f;
+        }
+        float mx = sa[0][0];
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) mx = fmaxf(mx, sa[kt][v]);
+        mx = quad_max(mx);
+        const float mnew = fmaxf(mrun[t], mx * sc);
+        const float alpha = __builtin_amdgcn_exp2f(mrun[t] - mnew);
+        mrun[t] = mnew;
+        float sum = 0.f;
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            float e = __builtin_amdgcn_exp2f(fmaf(sa[kt][v], sc, -mnew));
+            if (!ONES) sum += e;
+            pf[t & 1][kt >> 1][(kt & 1) * 4 + v] = (bf16_t)e;
+          }
+        if (!ONES) {
+          sum = quad_sum(sum);
+          lrun[t] = lrun[t] * alpha + sum;
+        }
+        // one matrix instruction per four vector instructions, as long as both last
+#pragma unroll
+        for (int i = 0; i < 4 * DK + 2 * DT; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, PIPE, 0);
+        }
+        if (__any(alpha != 1.0f)) {   // wave-uniform: some query of this tile moved its running max
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt) o[t][dt] *= alpha;
+        }
+      }
+      weighted_values(QT - 1, pf[(QT - 1) & 1]);
+    } else {
     // S^T tiles: rows = keys 16*kt + 4g + v, column = query li; every K fragment serves all QT query tiles
     f32x4 sacc[QT][4];
 #pragma unroll
@@ -255,6 +346,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
           o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[t][kk], o[t][dt], 0, 0, 0);
       }
     }
+    }
     // the other buffer was last read one iteration ago, before the barrier every wave has passed since
     if (more) store_tiles(buf ^ 1);
     __syncthreads();
@@ -283,16 +375,28 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnParams p) {
   }
 }
 
-template <int DK, int DT, int QT, bool ONES> void launch_qt(const AttnParams& p, hipStream_t s) {
+template <int DK, int DT, int QT, bool ONES, int PIPE> void launch_qt_p(const AttnParams& p, hipStream_t s) {
   constexpr int BQ = 4 * QT * 16;
   constexpr int LDS = 2 * (BKV * (DK * 64 + 16) + DT * 16 * (BKV * 2 + 16));
   static bool attr_set = false;
   if (!attr_set) {
-    hipFuncSetAttribute((const void*)attn_mfma_kernel<DK, DT, QT, ONES>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    hipFuncSetAttribute((const void*)attn_mfma_kernel<DK, DT, QT, ONES, PIPE>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     attr_set = true;
   }
   dim3 grid((p.Sq + BQ - 1) / BQ, p.heads, p.samples);
-  hipLaunchKernelGGL((attn_mfma_kernel<DK, DT, QT, ONES>), grid, dim3(256), LDS, s, p);
+  hipLaunchKernelGGL((attn_mfma_kernel<DK, DT, QT, ONES, PIPE>), grid, dim3(256), LDS, s, p);
+}
+
+// With two or more query tiles per wave the tile loop is software-pipelined (one matrix instruction per four vector
+// instructions: -4.5 % on the 4096-token, d = 40 self-attentions; ratios of 3 to 8 give the same).  Not at d = 160,
+// where the second set of score registers spills.
+template <int DK, int DT, int QT, bool ONES> void launch_qt(const AttnParams& p, hipStream_t s) {
+  constexpr int PIPE = QT >= 2 && DT <= 5 ? 4 : 0;
+#ifdef SDSTREAM_DEVHOOKS
+  static const bool no_pipe = getenv("SDSTREAM_ATTN_NOPIPE") != nullptr;
+  if (no_pipe) { launch_qt_p<DK, DT, QT, ONES, 0>(p, s); return; }
+#endif
+  launch_qt_p<DK, DT, QT, ONES, PIPE>(p, s);
 }
 
 // more query tiles per wave amortise the K / V fragment reads; fewer keep small problems spread over the chip
