@@ -73,6 +73,11 @@ struct IgemmParams {
   float ln_eps;
   float* stats_out;        // [M][ceil(N/BN)][2] partial sums of this layer's bf16-rounded output rows, one part per column tile; null = none
   int no_splitk;           // layers with ln_stats or stats_out never split K (their epilogue must see whole sums)
+  // GroupNorm statistics of this layer's output, left by its epilogue for the GroupNorm that follows (only the
+  // eight-wave 128 x 160 kernel does it; the launcher decides with gn_stats_splits): partial sums per
+  // (sample, row tile of the sample, group) in the layout the GroupNorm apply pass folds
+  float* gn_stats;         // [samples][Hout*Wout/128][gn_groups][2], or null
+  int gn_cg, gn_groups;    // channels per group (divides 160), groups of the whole output
   // MFMA direct-to-LDS kernels only: a second K segment behind the taps, a 1x1 convolution over the channel concat of
   // src3 | src4 (same pixels as the output: stride 1, no upsampling), K = ksize^2 (C1+C2) + C3 + C4.  All four
   // channel counts multiples of 64.  Used to sum a ResBlock's 1x1 skip convolution into its second 3x3 convolution.
@@ -91,7 +96,8 @@ struct IgemmParams {
 #define LN_MAX_PARTS 20   // most parts of row statistics a folded LayerNorm reads (column tiles of the producing layer)
 
 // Tile geometry the MFMA launcher will pick for p (M set): BN is what stats_out is indexed by.
-struct IgemmPlan { int variant, bm, bn, splitk; };
+// grouped: the launch takes the eight-wave kernel (two wave groups splitting the block's K range)
+struct IgemmPlan { int variant, bm, bn, splitk; bool grouped; };
 IgemmPlan igemm_mfma_plan(const IgemmParams& p);
 
 #define GN_MAX_SPLIT 64
@@ -139,6 +145,11 @@ void launch_igemm_mfma(const IgemmParams& p, hipStream_t s);
 bool igemm_mfma_supported(const IgemmParams& p);
 bool igemm_mfma_available();
 template <typename T> void launch_group_norm(const GroupNormParams& p, hipStream_t s);
+// bf16 GroupNorm whose statistics pass a producing layer can replace: true when the norm runs as the pair
+// (partial sums, apply) rather than as the single kernel of the small planes
+bool group_norm_takes_partials(const GroupNormParams& p);
+// the apply pass alone: p.stats already holds `splits` partial sums per (sample, group)
+void launch_group_norm_apply(const GroupNormParams& p, int splits, hipStream_t s);
 template <typename T> void launch_layer_norm(const LayerNormParams& p, hipStream_t s);
 template <typename T> void launch_attention_generic(const AttnParams& p, hipStream_t s);
 void launch_attention_mfma(const AttnParams& p, hipStream_t s);

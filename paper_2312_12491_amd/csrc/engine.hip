@@ -99,6 +99,8 @@ struct Op {
   int ln_src_op;         // >= 0: index of the op whose stats_out this op's folded LayerNorm reads
   int xattn_site;        // >= 0: a GEMM of a folded cross-attention: its weights belong to the prompt slot of each row
   int xattn_role;        //   1: rows x QK with softmax; 2: probabilities x VO
+  int gn_dst_plus1;      // GEMM op: 1 + index of the GroupNorm op that reads only this op's output, right after it (0: none)
+  int gn_src_plus1;      // GroupNorm op: 1 + index of that GEMM op (0: none)
   // conv_in / conv_out (fp32 NCHW <-> NHWC activations) and image_in / image_out (u8 HWC image <-> NHWC activations)
   const float* cw_f32;
   const void* cw;
@@ -417,6 +419,12 @@ struct Builder {
     p.out = aalloc((size_t)HW * (C1 + C2));
     op.rows_per_sample = HW;
     op.bytes_per_row = 2.0 * HW * (C1 + C2) * e.elt;
+    // a norm over the output of the layer just emitted: that layer's epilogue may leave the statistics (launch_op decides)
+    if (!s2 && !e.ops.empty() && e.ops.back().kind == OP_IGEMM && e.ops.back().mfma && e.ops.back().g.out == s1 &&
+        e.ops.back().xattn_site < 0) {
+      op.gn_src_plus1 = (int)e.ops.size();
+      e.ops.back().gn_dst_plus1 = (int)e.ops.size() + 1;
+    }
     e.ops.push_back(op);
     return p.out;
   }
@@ -1191,6 +1199,32 @@ IgemmParams mfma_params(sdstream* h, const Op& op0, int N) {
   return g;
 }
 
+// Row tiles per sample when the GEMM op `prod`, launched on N rows, leaves the GroupNorm statistics that the norm op
+// `gnop` right after it needs (the norm then runs its apply pass only); 0 when it does not.  Both launches ask here.
+int gn_stats_splits(sdstream* h, const Op& prod, const Op& gnop, int N) {
+#ifdef SDSTREAM_DEVHOOKS
+  static const bool off = getenv("SDSTREAM_NO_GNSTATS") != nullptr;
+  if (off) return 0;
+#endif
+  if (h->cfg.dtype != 1 || !prod.mfma) return 0;
+  GroupNormParams gp = gnop.gn;
+  gp.samples = N;
+  if (!group_norm_takes_partials(gp)) return 0;
+  const IgemmParams g = mfma_params(h, prod, N);
+  if (g.epilogue != EPI_NONE || g.stats_out || g.ln_stats) return 0;
+  const IgemmPlan pl = igemm_mfma_plan(g);
+  const int HW = prod.rows_per_sample, C = g.N;
+  if (C % gp.groups) return 0;
+  const int cg = C / gp.groups;
+  if (pl.variant == 3 && pl.bm == 64) {   // row-resident kernel, 64 rows x all 320 columns per block
+    if (HW % 64 || HW / 64 > GN_MAX_SPLIT || g.slot_m > 0) return 0;
+    return HW / 64;
+  }
+  if (!pl.grouped || pl.bn != 160 || pl.splitk != 1) return 0;
+  if (HW % 128 || HW / 128 > GN_MAX_SPLIT || C % 160 || 160 % cg) return 0;
+  return HW / 128;
+}
+
 void launch_op(sdstream* h, const Op& op0, int N, const int* kv_select, int xframe_rows, hipStream_t s) {
   const bool bf = h->cfg.dtype == 1;
   switch (op0.kind) {
@@ -1204,6 +1238,14 @@ void launch_op(sdstream* h, const Op& op0, int N, const int* kv_select, int xfra
           const IgemmParams pg = mfma_params(h, h->ops[op0.ln_src_op], N);
           const int bn = igemm_mfma_plan(pg).bn;
           g.ln_parts = (pg.N + bn - 1) / bn;
+        }
+        if (op0.gn_dst_plus1) {
+          const Op& gnop = h->ops[op0.gn_dst_plus1 - 1];
+          if (gn_stats_splits(h, op0, gnop, N)) {
+            g.gn_stats = gnop.gn.stats;
+            g.gn_groups = gnop.gn.groups;
+            g.gn_cg = g.N / gnop.gn.groups;
+          }
         }
         if (op0.xattn_site >= 0) {
           // The weights are per prompt: the rows of the positive prompt and those of the negative prompt (from row
@@ -1252,7 +1294,10 @@ void launch_op(sdstream* h, const Op& op0, int N, const int* kv_select, int xfra
     case OP_GN: {
       GroupNormParams p = op0.gn;
       p.samples = N;
-      if (bf) launch_group_norm<bf16_t>(p, s); else launch_group_norm<float>(p, s);
+      const int splits = op0.gn_src_plus1 ? gn_stats_splits(h, h->ops[op0.gn_src_plus1 - 1], op0, N) : 0;
+      if (splits) launch_group_norm_apply(p, splits, s);   // the layer before it left the partial sums
+      else if (bf) launch_group_norm<bf16_t>(p, s);
+      else launch_group_norm<float>(p, s);
       break;
     }
     case OP_LN: {

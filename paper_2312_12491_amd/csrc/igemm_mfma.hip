@@ -59,6 +59,18 @@ __device__ __forceinline__ float quad_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// sum over the 16 lanes of a DPP row (lanes that differ in lane % 16), left in every lane: four rotate-and-add steps
+template <int CTRL> __device__ __forceinline__ float dpp_rot(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float row16_sum(float x) {
+  x += dpp_rot<0x128>(x);   // row_ror:8
+  x += dpp_rot<0x124>(x);   // row_ror:4
+  x += dpp_rot<0x122>(x);   // row_ror:2
+  x += dpp_rot<0x121>(x);   // row_ror:1
+  return x;
+}
+
 // mean and 1/std of the block's input rows for a folded LayerNorm, from the partial sums the producing layer left:
 // thread r < BM folds the parts of row m0 + r and leaves (mean, rstd) in LDS for the epilogue.  (Requesting the
 // parts before the main loop and folding them after it, which takes the wait out of the prologue, was measured: it
@@ -159,13 +171,17 @@ __device__ __forceinline__ void epilogue_load(const IgemmParams& p, EpilogueIn<M
   }
 }
 
+// per lane: sum and sum of squares, over the wave's rows, of what is stored in each of the lane's 4 NT columns
+template <int NT> struct ColStats { float s[NT][4], q[NT][4]; };
+
 // lnrow / red: LDS, [rows of the block][2], already offset to this wave's first row; wn: the wave's column half;
-// ntile, ntiles: the block's column tile and their number (index of the row statistics it writes)
-template <int MT, int NT>
-__device__ __forceinline__ void epilogue_store(const IgemmParams& p, f32x4 (&acc)[MT][NT],
-                                               const EpilogueIn<MT, NT>& in, int mbase, int gnt0, int lane, int HWo,
-                                               int split, const float* lnrow, float* red, int wn, int ntile,
-                                               int ntiles) {
+// ntile, ntiles: the block's column tile and their number (index of the row statistics it writes);
+// cst: where the plain epilogue adds up the column statistics of the stored values (null: nowhere)
+template <int MT, int NT, bool CS>
+__device__ __forceinline__ void epilogue_store_cs(const IgemmParams& p, f32x4 (&acc)[MT][NT],
+                                                  const EpilogueIn<MT, NT>& in, int mbase, int gnt0, int lane, int HWo,
+                                                  int split, const float* lnrow, float* red, int wn, int ntile,
+                                                  int ntiles, ColStats<NT>& cst) {
   const int Nout = p.epilogue == EPI_GEGLU ? p.N >> 1 : p.N;
   if (p.ln_stats) {   // folded LayerNorm: rstd (x W'^T - mean wsum)
 #pragma unroll
@@ -309,6 +325,16 @@ __device__ __forceinline__ void epilogue_store(const IgemmParams& p, f32x4 (&acc
           ssq[mt] = fmaf(r, r, ssq[mt]);
         }
       }
+      if constexpr (CS) {
+        if (p.gn_stats) {
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const float r = (float)o[v];
+            cst.s[nt][v] += r;
+            cst.q[nt][v] = fmaf(r, r, cst.q[nt][v]);
+          }
+        }
+      }
     }
   }
   if (p.stats_out) {   // block-uniform: the two waves that share rows add up through LDS, one part per column tile
@@ -338,6 +364,15 @@ __device__ __forceinline__ void epilogue_store(const IgemmParams& p, f32x4 (&acc
       }
     }
   }
+}
+
+template <int MT, int NT>
+__device__ __forceinline__ void epilogue_store(const IgemmParams& p, f32x4 (&acc)[MT][NT],
+                                               const EpilogueIn<MT, NT>& in, int mbase, int gnt0, int lane, int HWo,
+                                               int split, const float* lnrow, float* red, int wn, int ntile,
+                                               int ntiles) {
+  ColStats<NT> none;
+  epilogue_store_cs<MT, NT, false>(p, acc, in, mbase, gnt0, lane, HWo, split, lnrow, red, wn, ntile, ntiles, none);
 }
 
 template <int BM, int BN, int NSETS>
@@ -863,8 +898,51 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void igemm_dma_kernel(Ig
 #pragma unroll
         for (int j = 0; j < NT; ++j) fin[i][j] = theirs[(i * NT + j) * 64] + acc[MH + i][j];
     }
-    epilogue_store<MH, NT>(p, fin, hin, m0 + row0, (n0 + wn * WTN) >> 4, lane, HWo, tile.split, lnrow + row0 * 2,
-                           red + row0 * 2, wn, tile.ntile, (int)ntiles.d);
+    ColStats<NT> cst;
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) { cst.s[j][v] = 0.f; cst.q[j][v] = 0.f; }
+    epilogue_store_cs<MH, NT, true>(p, fin, hin, m0 + row0, (n0 + wn * WTN) >> 4, lane, HWo, tile.split,
+                                    lnrow + row0 * 2, red + row0 * 2, wn, tile.ntile, (int)ntiles.d, cst);
+    if (p.gn_stats) {
+      // GroupNorm statistics of the block's 128 rows x BN columns for the norm that follows (block-uniform branch;
+      // the launcher has checked that the rows lie in one sample and that groups do not straddle column tiles):
+      // columns over the 16 lanes of a row, then over the four waves that share the columns, then channels to groups.
+      // Every sum is taken in a fixed order.
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          cst.s[j][v] = row16_sum(cst.s[j][v]);
+          cst.q[j][v] = row16_sum(cst.q[j][v]);
+        }
+      float* cred = (float*)lds;   // [4 row groups][BN columns][2]
+      __syncthreads();             // the accumulator exchange above is read
+      if ((lane & 15) == 0) {
+        const int rg = grp * 2 + wm;
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int col = wn * WTN + j * 16 + (lane >> 4) * 4 + v;
+            cred[(rg * BN + col) * 2] = cst.s[j][v];
+            cred[(rg * BN + col) * 2 + 1] = cst.q[j][v];
+          }
+      }
+      __syncthreads();
+      const int cg = p.gn_cg, gtile = BN / cg;
+      if (tid < gtile * 2) {   // one thread per (group, sum | sum of squares)
+        const int gi = tid >> 1, st = tid & 1;
+        float a = 0.f;
+        for (int c = gi * cg; c < (gi + 1) * cg; ++c)
+          a += (cred[(0 * BN + c) * 2 + st] + cred[(1 * BN + c) * 2 + st]) +
+               (cred[(2 * BN + c) * 2 + st] + cred[(3 * BN + c) * 2 + st]);
+        const int smp = fast_div(m0, p.fd_hw);
+        const int sp = (m0 - smp * HWo) / BM, nsp = HWo / BM;
+        p.gn_stats[(((long long)smp * nsp + sp) * p.gn_groups + n0 / cg + gi) * 2 + st] = a;
+      }
+    }
   } else {
     if constexpr (BM != 64) epilogue_load<MT, NT>(p, epi_in, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo);
     epilogue_store<MT, NT>(p, acc, epi_in, m0 + wm * WTM, (n0 + wn * WTN) >> 4, lane, HWo, tile.split,
@@ -992,6 +1070,11 @@ __global__ __launch_bounds__(64 * WAVES, 1) void igemm_rows_kernel(IgemmParams p
     }
     // epilogue of this kernel's layers: folded LayerNorm, bias, then GEGLU (value and gate tiles side by side) or
     // residual and plain store, with the row sums of what is stored for a LayerNorm folded into the next layer
+    ColStats<NT> cst;   // short shape: column sums of what is stored, for a GroupNorm that follows
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) { cst.s[j][v] = 0.f; cst.q[j][v] = 0.f; }
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       const int r = mt * 16 + (lane & 15), m = m0 + r;
@@ -1036,6 +1119,10 @@ __global__ __launch_bounds__(64 * WAVES, 1) void igemm_rows_kernel(IgemmParams p
             const float a = (float)o0[v], b = (float)o1[v];
             ssum += a + b;
             ssq = fmaf(a, a, fmaf(b, b, ssq));
+            if constexpr (BM == 64) {
+              cst.s[0][v] += a; cst.q[0][v] = fmaf(a, a, cst.q[0][v]);
+              cst.s[1][v] += b; cst.q[1][v] = fmaf(b, b, cst.q[1][v]);
+            }
           }
         }
       }
@@ -1050,9 +1137,38 @@ __global__ __launch_bounds__(64 * WAVES, 1) void igemm_rows_kernel(IgemmParams p
         }
       }
     }
+    if constexpr (BM == 64) {
+      if (p.gn_stats) {   // block-uniform: this wave's 32 channel sums over the block's rows, into LDS
+        float* cred = red + WAVES * BM * 2;   // [N columns][2]
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const float a = row16_sum(cst.s[j][v]), b = row16_sum(cst.q[j][v]);
+            if ((lane & 15) == 0) {
+              const int col = slice * 32 + j * 16 + ncol + v;
+              cred[col * 2] = a;
+              cred[col * 2 + 1] = b;
+            }
+          }
+      }
+    }
   }
   if constexpr (BM == 64) {
     // every wave of the short shape has exactly one slice (the launcher sees to it), so all of them arrive here
+    if (p.gn_stats) {   // channels to groups: one thread per (group, sum | sum of squares); the rows lie in one sample
+      __syncthreads();
+      const float* cred = red + WAVES * BM * 2;
+      const int cg = p.gn_cg;
+      if (tid < p.gn_groups * 2) {
+        const int gi = tid >> 1, st = tid & 1;
+        float a = 0.f;
+        for (int c = gi * cg; c < (gi + 1) * cg; ++c) a += cred[c * 2 + st];
+        const int HWo = p.Hout * p.Wout;
+        const int smp = m0 / HWo, sp = (m0 - smp * HWo) / BM, nsp = HWo / BM;
+        p.gn_stats[(((long long)smp * nsp + sp) * p.gn_groups + gi) * 2 + st] = a;
+      }
+    }
     if (p.stats_out) {
       __syncthreads();
       if (tid < BM && m0 + tid < p.M) {
@@ -1153,7 +1269,7 @@ int rows_kernel_shape(const IgemmParams& p) {
 }
 
 template <int KSTEPS, int BM, int WAVES> void launch_rows_t(const IgemmParams& p, int nsplit, hipStream_t s) {
-  constexpr int LDS = (KSTEPS / 2) * BM * 128 + BM * 8 + WAVES * BM * 8;
+  constexpr int LDS = (KSTEPS / 2) * BM * 128 + BM * 8 + WAVES * BM * 8 + (BM == 64 ? 320 * 8 : 0);
   static bool attr_set = false;
   if (!attr_set) {
     hipFuncSetAttribute((const void*)igemm_rows_kernel<KSTEPS, BM, WAVES>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
@@ -1315,7 +1431,8 @@ template <int BM, int BN> void launch_ring(const IgemmParams& p, hipStream_t s) 
   if constexpr (BM == 128) {
     const int splitk = p.splitk > 1 ? p.splitk : 1;
     const int stages = (p.K / 64 + splitk - 1) / splitk;
-    if (one_per_unit && stages >= group_min) { launch_dma<BM, BN, 2, false, 2>(p, s); return; }
+    // (a launch that is to leave GroupNorm statistics was planned as a grouped one: only that kernel writes them)
+    if ((one_per_unit && stages >= group_min) || p.gn_stats) { launch_dma<BM, BN, 2, false, 2>(p, s); return; }
   }
   if (three) launch_dma<BM, BN, 3, true>(p, s);
   else launch_dma<BM, BN, 2, false>(p, s);
@@ -1344,6 +1461,12 @@ IgemmPlan igemm_mfma_plan(const IgemmParams& p) {
     const int stages = c.variant == 0 ? p.K / 32 : p.K / 64;
     const int sps = (stages + r.splitk - 1) / r.splitk;
     r.splitk = (stages + sps - 1) / sps;
+  }
+  r.grouped = false;
+  if (r.variant == 1) {   // (the rule of launch_ring)
+    const int blocks = ((p.M + 127) / 128) * ((p.N + r.bn - 1) / r.bn) * r.splitk;
+    const int stages = (p.K / 64 + r.splitk - 1) / r.splitk;
+    r.grouped = blocks <= 256 && stages >= kGroupSplitMinStages;
   }
   return r;
 }

@@ -409,6 +409,18 @@ bool gn_fast_ok(const GroupNormParams& p) {
          ((size_t)gn_lanes(C / 8) + 1) * C * 2 * sizeof(float) <= 160 * 1024;
 }
 
+// pass 2: four pixels per thread, one trip of the loop (measured inside the step: 1 / 2 / 3 / 4 / 8 pixels ->
+// 293 / 211 / 191 / 196 / 198 us over the 30 launches of a step)
+void launch_gn_apply(const GroupNormParams& p, int nsplit_p, hipStream_t s) {
+  const int C = p.C1 + p.C2, chunks = C / 8;
+  const int lanes = gn_lanes(chunks);
+  const int threads = chunks * lanes;
+  const int ppb = 4 * lanes;
+  const int nsplit = (p.HW + ppb - 1) / ppb;
+  hipLaunchKernelGGL(gn_apply_bf16_kernel, dim3(p.samples * nsplit), dim3(threads), (size_t)p.groups * 2 * sizeof(float),
+                     s, p, ppb, nsplit, chunks, lanes, nsplit_p);
+}
+
 void launch_gn_fast(const GroupNormParams& p, hipStream_t s) {
   GnFusedPlan f;
   if (gn_fused_plan(p, f)) {
@@ -429,15 +441,16 @@ void launch_gn_fast(const GroupNormParams& p, hipStream_t s) {
   const int nsplit_p = (p.HW + ppb_p - 1) / ppb_p;
   hipLaunchKernelGGL(gn_partial_bf16_kernel, dim3(p.samples * nsplit_p), dim3(threads),
                      ((size_t)lanes + 1) * C * 2 * sizeof(float), s, p, ppb_p, nsplit_p, chunks, lanes);
-  // pass 2: four pixels per thread, one trip of the loop (measured inside the step: 1 / 2 / 3 / 4 / 8 pixels ->
-  // 293 / 211 / 191 / 196 / 198 us over the 30 launches of a step)
-  const int ppb = 4 * lanes;
-  const int nsplit = (p.HW + ppb - 1) / ppb;
-  hipLaunchKernelGGL(gn_apply_bf16_kernel, dim3(p.samples * nsplit), dim3(threads), (size_t)p.groups * 2 * sizeof(float),
-                     s, p, ppb, nsplit, chunks, lanes, nsplit_p);
+  launch_gn_apply(p, nsplit_p, s);
 }
 
 }  // namespace
+
+bool group_norm_takes_partials(const GroupNormParams& p) {
+  GnFusedPlan f;
+  return gn_fast_ok(p) && !gn_fused_plan(p, f);
+}
+void launch_group_norm_apply(const GroupNormParams& p, int splits, hipStream_t s) { launch_gn_apply(p, splits, s); }
 
 template <typename T> void launch_group_norm_generic(const GroupNormParams& p, hipStream_t s);
 
