@@ -505,8 +505,53 @@ __global__ __launch_bounds__(256) void mfma_ceiling_kernel(int iters, float* sin
   for (int i = 0; i < 8; ++i) t += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
   if (t == -1.0f) sink[0] = t;  // never true (all products are >= 0): keeps the chains alive without a store
 }
+#ifdef SDSTREAM_DEVHOOKS
+// development probe: the same chains with NV independent vector fused multiply-adds (and NE v_exp_f32) after every
+// matrix instruction - do the two pipes overlap within a SIMD?  (The reported rate still counts the MFMAs only.)
+template <int NV, int NE>
+__global__ __launch_bounds__(256) void mfma_valu_probe_kernel(int iters, float* sink) {
+  probe_bf16x8 a, b;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    a[e] = (__bf16)(float)((threadIdx.x + e) & 3);
+    b[e] = (__bf16)(float)((threadIdx.x * 3 + e) & 1);
+  }
+  probe_f32x4 acc[8];
+  float f[8], x[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { acc[i] = probe_f32x4{0.f, 0.f, 0.f, 0.f}; f[i] = 1.0f + threadIdx.x * 1e-9f; x[i] = -threadIdx.x * 1e-3f; }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if (NV >= 0) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc[i]) : "v"(a), "v"(b));
+#pragma unroll
+      for (int k = 0; k < (NV < 0 ? -NV : NV); ++k) asm volatile("v_fma_f32 %0, %0, %1, %0" : "+v"(f[(i + k) & 7]) : "v"(f[0]));
+#pragma unroll
+      for (int k = 0; k < NE; ++k) asm volatile("v_exp_f32 %0, %0" : "+v"(x[(i + k) & 7]));
+    }
+  }
+  float t = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) t += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3] + f[i] + x[i];
+  if (t == -1.0f) sink[0] = t;
+}
+#endif
 }  // namespace
 
 void launch_mfma_ceiling(int iters, int blocks, float* sink, hipStream_t s) {
+#ifdef SDSTREAM_DEVHOOKS
+  static const int nv = getenv("SDSTREAM_CEIL_VALU") ? atoi(getenv("SDSTREAM_CEIL_VALU")) : 0;
+  switch (nv) {   // positive: MFMA + that many v_fma; negative: the v_fma alone; 100 + n: MFMA + n v_exp
+    case 1: hipLaunchKernelGGL((mfma_valu_probe_kernel<1, 0>), dim3(blocks), dim3(256), 0, s, iters, sink); return;
+    case 2: hipLaunchKernelGGL((mfma_valu_probe_kernel<2, 0>), dim3(blocks), dim3(256), 0, s, iters, sink); return;
+    case 3: hipLaunchKernelGGL((mfma_valu_probe_kernel<3, 0>), dim3(blocks), dim3(256), 0, s, iters, sink); return;
+    case 4: hipLaunchKernelGGL((mfma_valu_probe_kernel<4, 0>), dim3(blocks), dim3(256), 0, s, iters, sink); return;
+    case -2: hipLaunchKernelGGL((mfma_valu_probe_kernel<-2, 0>), dim3(blocks), dim3(256), 0, s, iters, sink); return;
+    case -4: hipLaunchKernelGGL((mfma_valu_probe_kernel<-4, 0>), dim3(blocks), dim3(256), 0, s, iters, sink); return;
+    case 101: hipLaunchKernelGGL((mfma_valu_probe_kernel<0, 1>), dim3(blocks), dim3(256), 0, s, iters, sink); return;
+    case 102: hipLaunchKernelGGL((mfma_valu_probe_kernel<2, 1>), dim3(blocks), dim3(256), 0, s, iters, sink); return;
+    default: break;
+  }
+#endif
   hipLaunchKernelGGL(mfma_ceiling_kernel, dim3(blocks), dim3(256), 0, s, iters, sink);
 }
