@@ -389,7 +389,8 @@ template <int DK, int DT, int QT, bool ONES, int PIPE> void launch_qt_p(const At
 
 // With two or more query tiles per wave the tile loop is software-pipelined (one matrix instruction per four vector
 // instructions: -4.5 % on the 4096-token, d = 40 self-attentions; ratios of 3 to 8 give the same).  Not at d = 160,
-// where the second set of score registers spills.
+// where the second set of score registers spills.  (Key tiles of 128 instead of 64 keys per barrier, multiplied as
+// two halves, were measured too: 149.4 against 147.7 us - the hand-over between tiles is not what is left.)
 template <int DK, int DT, int QT, bool ONES> void launch_qt(const AttnParams& p, hipStream_t s) {
   constexpr int PIPE = QT >= 2 && DT <= 5 ? 4 : 0;
 #ifdef SDSTREAM_DEVHOOKS
