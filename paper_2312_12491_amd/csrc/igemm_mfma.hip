@@ -158,6 +158,9 @@ __device__ __forceinline__ void epilogue_load(const IgemmParams& p, EpilogueIn<M
     in.rbv[nt] = *(const f32x4*)rsrc;
     in.wsv[nt] = *(const f32x4*)(p.ln_wsum ? p.ln_wsum + voff + n : (const float*)p.zeros);
   }
+#ifdef SDSTREAM_DEVHOOKS
+  if (p.dev_exp & 16384) res = nullptr;
+#endif
   if (res && p.epilogue != EPI_GEGLU) {   // (plain and ReLU epilogues)
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
@@ -316,6 +319,9 @@ __device__ __forceinline__ void epilogue_store_cs(const IgemmParams& p, f32x4 (&
       bf16x4 o;
 #pragma unroll
       for (int v = 0; v < 4; ++v) o[v] = (bf16_t)x[v];
+#ifdef SDSTREAM_DEVHOOKS
+      if (!((p.dev_exp & 8192) && x[0] != 12345.678f))
+#endif
       *(bf16x4*)(out + (long long)m * Nout + n) = o;
       if (p.stats_out) {
 #pragma unroll
@@ -735,6 +741,7 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void igemm_dma_kernel(Ig
       const char* g = okv[i] ? aptr[i] : zeros;
 #ifdef SDSTREAM_DEVHOOKS
       if (p.dev_exp & 256) g = zeros;
+      if (p.dev_exp & 4096) continue;
 #endif
       lds_dma16(g, sa + (i * NW + wave) * 1024);
     }
@@ -743,6 +750,7 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void igemm_dma_kernel(Ig
       const char* g = bptr[i];
 #ifdef SDSTREAM_DEVHOOKS
       if (p.dev_exp & 512) g = zeros;
+      if (p.dev_exp & 2048) continue;
 #endif
       lds_dma16(g, sa + ABYTES + (i * NW + wave) * 1024);
     }
