@@ -78,6 +78,13 @@ struct IgemmParams {
   // (sample, row tile of the sample, group) in the layout the GroupNorm apply pass folds
   float* gn_stats;         // [samples][Hout*Wout/128][gn_groups][2], or null
   int gn_cg, gn_groups;    // channels per group (divides 160), groups of the whole output
+  // GroupNorm (scale and shift, no activation) applied to this layer's INPUT rows as they sit in LDS (64-row
+  // row-resident kernel only; the launcher decides): the partial sums of the norm's statistics, as above, and its vectors
+  const float* gn_in_stats;   // [samples][gn_in_splits][gn_in_groups][2], or null
+  const float* gn_in_gamma;
+  const float* gn_in_beta;
+  int gn_in_splits, gn_in_groups;
+  float gn_in_eps;
   // MFMA direct-to-LDS kernels only: a second K segment behind the taps, a 1x1 convolution over the channel concat of
   // src3 | src4 (same pixels as the output: stride 1, no upsampling), K = ksize^2 (C1+C2) + C3 + C4.  All four
   // channel counts multiples of 64.  Used to sum a ResBlock's 1x1 skip convolution into its second 3x3 convolution.

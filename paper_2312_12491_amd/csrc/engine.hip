@@ -101,6 +101,8 @@ struct Op {
   int xattn_role;        //   1: rows x QK with softmax; 2: probabilities x VO
   int gn_dst_plus1;      // GEMM op: 1 + index of the GroupNorm op that reads only this op's output, right after it (0: none)
   int gn_src_plus1;      // GroupNorm op: 1 + index of that GEMM op (0: none)
+  int gn_in_plus1;       // GEMM op: 1 + index of the GroupNorm op right before it whose output only this op reads (0: none)
+  int gn_out_plus1;      // GroupNorm op: 1 + index of that GEMM op (0: none)
   // conv_in / conv_out (fp32 NCHW <-> NHWC activations) and image_in / image_out (u8 HWC image <-> NHWC activations)
   const float* cw_f32;
   const void* cw;
@@ -380,6 +382,7 @@ struct Builder {
   void afree(void* p) { e.act.release((size_t)((char*)p - e.act_base) / (size_t)e.max_batch); }
 
   // ---- ops
+  bool norm_only_here = false;   // set around the emission of a layer that is the only reader of the norm before it
   void* conv(const void* s1, int C1, const void* s2, int C2, int Hin, int Win, int Hout, int Wout, int ks, int stride,
              int ups, const LinW& w, const float* rowbias, int rowbias_ld, const void* residual, int epi) {
     Op op{};
@@ -399,6 +402,12 @@ struct Builder {
     g.splitk = 1;
     op.ln_src_op = -1;
     op.xattn_site = -1;
+    // the layer reads the output of the norm just emitted, and nothing else does (the caller says so by passing
+    // norm_only_here): the norm may be applied to this layer's input rows on load instead (launch_op decides)
+    if (norm_only_here && !s2 && !e.ops.empty() && e.ops.back().kind == OP_GN && e.ops.back().gn.out == s1 && w.mfma) {
+      op.gn_in_plus1 = (int)e.ops.size();
+      e.ops.back().gn_out_plus1 = (int)e.ops.size() + 1;
+    }
     int Nout = epi == EPI_GEGLU ? w.N / 2 : w.N;
     g.out = aalloc((size_t)Hout * Wout * Nout);
     op.rows_per_sample = Hout * Wout;
@@ -639,7 +648,9 @@ struct Builder {
     LinW pout = matw(p + ".proj_out", C, C, 1, false, true, false, C, 0);
 
     void* t = gn(x, C, nullptr, 0, HW, 1e-6f, 0, gng, gnb, stats_buf());
+    norm_only_here = true;   // (t is read by proj_in alone; x stays allocated as the block's residual)
     void* h = conv(t, C, nullptr, 0, H, W, H, W, 1, 1, 0, pin, nullptr, 0, nullptr, EPI_NONE);
+    norm_only_here = false;
     // With the matrix-core kernels the three LayerNorms are folded into the layers that consume them: the producer of
     // the rows (proj_in, the two attention output projections) leaves per-row partial sums, the consumer (q/k/v, the
     // cross-attention q, the feed-forward input) multiplies the raw rows by weights pre-scaled with the norm's scale.
@@ -1225,6 +1236,24 @@ int gn_stats_splits(sdstream* h, const Op& prod, const Op& gnop, int N) {
   return HW / 128;
 }
 
+// Statistics splits when the norm op `gnop` is not launched at all on N rows: the layer before it leaves its
+// statistics AND the layer after it (`cons`, the 64-row row-resident kernel) applies it to its input rows on load.
+// 0 when the norm runs as a kernel.  Both the norm's and the consumer's launch ask here.
+int gn_applied_on_load(sdstream* h, const Op& gnop, const Op& cons, int N) {
+#ifdef SDSTREAM_DEVHOOKS
+  static const bool off = getenv("SDSTREAM_NO_GNLOAD") != nullptr;
+  if (off) return 0;
+#endif
+  if (!gnop.gn_src_plus1 || gnop.gn.silu || gnop.gn.src2) return 0;
+  const int splits = gn_stats_splits(h, h->ops[gnop.gn_src_plus1 - 1], gnop, N);
+  if (!splits) return 0;
+  const IgemmParams g = mfma_params(h, cons, N);
+  const IgemmPlan pl = igemm_mfma_plan(g);
+  if (pl.variant != 3 || pl.bm != 64 || g.C1 != 320 || g.C1 != gnop.gn.C1 || g.C1 % gnop.gn.groups) return 0;
+  if (cons.rows_per_sample % 64 || gnop.gn.HW != cons.rows_per_sample) return 0;
+  return splits;
+}
+
 void launch_op(sdstream* h, const Op& op0, int N, const int* kv_select, int xframe_rows, hipStream_t s) {
   const bool bf = h->cfg.dtype == 1;
   switch (op0.kind) {
@@ -1238,6 +1267,19 @@ void launch_op(sdstream* h, const Op& op0, int N, const int* kv_select, int xfra
           const IgemmParams pg = mfma_params(h, h->ops[op0.ln_src_op], N);
           const int bn = igemm_mfma_plan(pg).bn;
           g.ln_parts = (pg.N + bn - 1) / bn;
+        }
+        if (op0.gn_in_plus1) {
+          const Op& gnop = h->ops[op0.gn_in_plus1 - 1];
+          const int splits = gn_applied_on_load(h, gnop, op0, N);
+          if (splits) {   // the norm was not launched: its input, statistics and vectors come here
+            g.src1 = gnop.gn.src1;
+            g.gn_in_stats = gnop.gn.stats;
+            g.gn_in_gamma = gnop.gn.gamma;
+            g.gn_in_beta = gnop.gn.beta;
+            g.gn_in_splits = splits;
+            g.gn_in_groups = gnop.gn.groups;
+            g.gn_in_eps = gnop.gn.eps;
+          }
         }
         if (op0.gn_dst_plus1) {
           const Op& gnop = h->ops[op0.gn_dst_plus1 - 1];
@@ -1294,6 +1336,7 @@ void launch_op(sdstream* h, const Op& op0, int N, const int* kv_select, int xfra
     case OP_GN: {
       GroupNormParams p = op0.gn;
       p.samples = N;
+      if (op0.gn_out_plus1 && gn_applied_on_load(h, op0, h->ops[op0.gn_out_plus1 - 1], N)) break;   // nothing to launch
       const int splits = op0.gn_src_plus1 ? gn_stats_splits(h, h->ops[op0.gn_src_plus1 - 1], op0, N) : 0;
       if (splits) launch_group_norm_apply(p, splits, s);   // the layer before it left the partial sums
       else if (bf) launch_group_norm<bf16_t>(p, s);

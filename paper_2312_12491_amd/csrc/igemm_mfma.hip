@@ -1019,6 +1019,62 @@ __global__ __launch_bounds__(64 * WAVES, 1) void igemm_rows_kernel(IgemmParams p
   const int a_x = ((lane & 15) >> 1) & 7;   // (row >> 1) & 7 with row = mt * 16 + lane % 16
   __builtin_amdgcn_s_waitcnt(0x0F70 | 0 | (0 << 14));   // vmcnt(0): the rows (and the first fragments) have landed
   __syncthreads();
+  if constexpr (BM == 64) {
+    if (p.gn_in_stats) {
+      // GroupNorm of the input rows, in place in LDS, with the arithmetic of the norm's own apply pass (partial sums
+      // folded in double in a fixed order, y = fma(x, rstd gamma, beta - mean rstd gamma), rounded to bf16): what
+      // this layer multiplies is bit for bit what that pass would have written.  The block's rows lie in one sample.
+      float* gmr = red;   // [groups][2] mean, rstd (the row-statistics area is not in use yet)
+      const int HWo = p.Hout * p.Wout, smp = m0 / HWo;
+      const int groups = p.gn_in_groups, cg = K / groups, nsp = p.gn_in_splits;
+      for (int idx = tid; idx < groups * 8; idx += 64 * WAVES) {
+        const int gi = idx >> 3, part = idx & 7;
+        double ss = 0.0, qq = 0.0;
+        for (int k = part; k < nsp; k += 8) {
+          const float* src = p.gn_in_stats + (((long long)smp * nsp + k) * groups + gi) * 2;
+          ss += src[0];
+          qq += src[1];
+        }
+#pragma unroll
+        for (int o = 1; o < 8; o <<= 1) {
+          ss += __shfl_xor(ss, o);
+          qq += __shfl_xor(qq, o);
+        }
+        if (part == 0) {
+          const double cnt = (double)HWo * cg;
+          const double mean = ss / cnt;
+          double var = qq / cnt - mean * mean;
+          if (var < 0) var = 0;
+          gmr[gi * 2] = (float)mean;
+          gmr[gi * 2 + 1] = (float)(1.0 / sqrt(var + (double)p.gn_in_eps));
+        }
+      }
+      __syncthreads();
+      float* scsh = gmr + groups * 2;   // [K][2] scale, shift per channel
+      for (int ch = tid; ch < K; ch += 64 * WAVES) {
+        const int gi = ch / cg;
+        const float rs = gmr[gi * 2 + 1] * p.gn_in_gamma[ch];
+        scsh[ch * 2] = rs;
+        scsh[ch * 2 + 1] = p.gn_in_beta[ch] - gmr[gi * 2] * rs;
+      }
+      __syncthreads();
+      constexpr int CHUNKS = KSTEPS * 4;   // 16-byte chunks per row
+      for (int i = tid; i < BM * CHUNKS; i += 64 * WAVES) {
+        const int r = i / CHUNKS, c = i - r * CHUNKS;
+        bf16x8* cell = (bf16x8*)(lds + (c >> 3) * (BM * 128) + r * 128 + (((c & 7) ^ ((r >> 1) & 7)) << 4));
+        bf16x8 v = *cell;
+        const f32x4* ss = (const f32x4*)(scsh + c * 16);   // (scale, shift) of the chunk's 8 channels
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+          const f32x4 t = ss[e >> 1];
+          v[e] = (bf16_t)fmaf((float)v[e], t[0], t[1]);
+          v[e + 1] = (bf16_t)fmaf((float)v[e + 1], t[2], t[3]);
+        }
+        *cell = v;
+      }
+      __syncthreads();
+    }
+  }
 
   const int ncol = (lane >> 4) * 4;
   const float* zf = (const float*)p.zeros;
