@@ -5,9 +5,11 @@
 // Work split: one 256-thread block (4 waves, 2x2) owns a BM x BN output tile.  The activation tile (implicit
 // im2col rows gathered from NHWC, with zero padding, stride, nearest-2x upsample and a second, concatenated
 // source folded into the indexing) and the weight tile (stored pre-packed in MFMA fragment order) are staged
-// through double-buffered LDS.  Two kernels: the main one moves both operands global -> LDS directly in 64-deep
-// K stages (channels a multiple of 64); the other stages activations through registers in 32-deep stages and
-// reads weight fragments straight into registers (channels a multiple of 32).  The MFMA is issued with the
+// through LDS buffers.  Three kernels: the main one (igemm_dma_kernel) moves both operands global -> LDS directly in
+// 64-deep K stages (channels a multiple of 64), in one of three pipeline shapes (launch_ring); igemm_mfma_kernel
+// stages activations through registers in 32-deep stages and reads weight fragments straight into registers
+// (channels a multiple of 32); igemm_rows_kernel, for 1x1 layers with K <= 640 on many rows, keeps a block's input
+// rows in LDS for the whole launch and streams the weights through registers, without barriers.  The MFMA is issued with the
 // weight fragment as the row operand, so every lane ends up with 4 consecutive output channels of one pixel:
 // bias, time-embedding bias, GEGLU and the residual are applied on registers and stored as 8-byte vectors.
 // Optional split-K writes fp32 partial tiles to a workspace that a small finalize kernel sums and turns into
